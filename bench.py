@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Throughput of the Encode stage (ViT forward, V_m = E(I_m); paper section 3.1, Eq. 1) on one
+MI355X: visual tokens per second on the 24-layer bf16 encoder with a batch of 8 images of
+448 x 448 (6272 packed patch tokens -> 1568 visual tokens), synthetic seeded inputs.
+
+One "step" is one epd_encode call: plan, patch embedding, 24 transformer blocks, final norm,
+2x2 merge and projection, with the packed patches and weights already resident in HBM.
+
+Prints ONE JSON line on stdout; progress and the per-step table go to stderr.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix-core peak
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(cfg, gw, layers, patches, cu, grid, gpu_out, n_items):
+    """Time the CPU oracle, as it stands, on the first n_items images of the same batch."""
+    from oracle import vit_encode as O
+    from paper_2601_11590_amd import workloads as W
+    grids = [tuple(int(v) for v in g) for g in grid[:n_items]]
+    T = W.num_tokens(grids)
+    Tm = W.num_merged_tokens(grids, cfg.merge)
+    cu1, g1 = W.metadata(grids)
+    t0 = time.perf_counter()
+    ref = O.encode(cfg, gw, layers, patches[:T], cu1, g1)
+    dt = time.perf_counter() - t0
+    got = gpu_out[:Tm].astype(np.float64)
+    cos = (got * ref).sum(-1) / (np.linalg.norm(got, axis=-1) * np.linalg.norm(ref, axis=-1))
+    rel = np.abs(got - ref).max(-1) / np.abs(ref).max(-1)
+    log("[bench] oracle on %d image(s): %.2f s; GPU rows vs oracle: min cos %.6f, max rel %.3e"
+        % (n_items, dt, cos.min(), rel.max()))
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit():
+        cores = min(cores, int(env))
+    return {"value": Tm / dt, "unit": "visual tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d of the 8 images (%d patch tokens -> %d visual tokens), all %d layers, "
+                      "fp64 NumPy, one run" % (n_items, T, Tm, cfg.num_layers),
+            "seconds": dt, "parity_min_cos": float(cos.min()), "parity_max_rel": float(rel.max())}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C2", help="C2 (headline) | C3 | C4 | C5 (other single-GPU shapes)")
+    ap.add_argument("--layers", type=int, default=None, help="override depth (non-headline experiments only)")
+    ap.add_argument("--cpu-items", type=int, default=1, help="images of the batch the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+            "--gpus %d is not supported. Items would shard across GPUs by image with replicated "
+            "weights; nothing here launches more than one rank." % args.gpus)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_11590_amd import binding as B, workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    cfg = W.CONFIGS[args.config]
+    grids = W.grids_for(cfg)
+    if args.layers is not None:
+        cfg = cfg.replace(num_layers=args.layers)
+    T, Tm = W.num_tokens(grids), W.num_merged_tokens(grids, cfg.merge)
+    log("[bench] %s: %d items, T=%d patch tokens -> %d visual tokens, L=%d" % (cfg.name, len(grids), T, Tm, cfg.num_layers))
+
+    t0 = time.perf_counter()
+    gw = W.global_weights(cfg)
+    layers = [W.layer_weights(cfg, l) for l in range(cfg.num_layers)]
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids)
+    log("[bench] inputs generated in %.1f s" % (time.perf_counter() - t0))
+
+    enc = B.EpdEncoder(cfg, gw, layers, max_tokens=T, max_segments=len(cu) - 1, max_items=len(grids))
+    p_dev = B.to_device_patches(patches, cfg.dtype)
+    out = torch.empty((Tm, cfg.out_dim), dtype=B.torch_dtype(cfg.dtype), device="cuda:0")
+    log("[bench] workspace %.2f GB" % (enc.workspace_bytes / 1e9))
+
+    # ---- warm-up, with a per-step timing pass to find the dominant kernel
+    for _ in range(max(1, args.warmup)):
+        enc.encode(p_dev, cu, grid, out)
+    torch.cuda.synchronize()
+    table = {}
+    for step in range(B.EPD_STEP_COUNT):
+        enc.set_timing(step)
+        enc.encode(p_dev, cu, grid, out)
+        torch.cuda.synchronize()
+        ms, n, work = enc.get_timing()
+        table[B.STEP_NAMES[step]] = (ms, n, work)
+    enc.set_timing(-1)
+    tot = sum(v[0] for v in table.values())
+    log("[bench] per-step kernel time of one call (HIP events around each launch):")
+    for k, (ms, n, work) in table.items():
+        if n == 0:
+            continue
+        rate = work / (ms * 1e-3) if ms > 0 else 0.0
+        unit = "GB/s" if k == "norm" else "TFLOP/s"
+        scale = 1e9 if k == "norm" else 1e12
+        log("    %-12s %4d launches %9.3f ms  %5.1f%%  %8.1f %s" % (k, n, ms, 100 * ms / tot, rate / scale, unit))
+    mat_steps = [k for k in table if k not in ("plan", "norm") and table[k][1] > 0]
+    dom = max(mat_steps, key=lambda k: table[k][0])
+    dom_id = B.STEP_NAMES.index(dom)
+
+    # ---- timed region: exactly K steps; the dominant kernel is bracketed by HIP events
+    enc.set_timing(dom_id)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        enc.encode(p_dev, cu, grid, out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    dom_ms, dom_n, dom_work = enc.get_timing()
+    enc.set_timing(-1)
+
+    ms_per_step = dt / args.steps * 1e3
+    value = Tm * args.steps / dt
+    achieved = dom_work / (dom_ms * 1e-3) / 1e12          # TFLOP/s over the kernel's own time
+    D, F, L = cfg.hidden, cfg.mlp_dim, cfg.num_layers
+    flops_call = (2.0 * T * cfg.patch_dim * D + L * (8.0 * T * D * D + 4.0 * T * D * F)
+                  + L * sum(4.0 * float(cu[i + 1] - cu[i]) ** 2 * D for i in range(len(cu) - 1))
+                  + 2.0 * Tm * (cfg.merge ** 2 * D) * cfg.out_dim)
+    log("[bench] %.3f ms/step, %.0f visual tokens/s, %.1f TFLOP/s end to end (%.1f%% of bf16 peak)"
+        % (ms_per_step, value, flops_call / (ms_per_step * 1e-3) / 1e12,
+           100 * flops_call / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS))
+
+    gpu_out = out.float().cpu().numpy()
+    cpu = None
+    if args.cpu_items > 0:
+        cpu = cpu_baseline(cfg, gw, layers, patches, cu, grid, gpu_out, min(args.cpu_items, len(grids)))
+
+    res = {
+        "metric": "visual tokens/sec (ViT encode fwd, 1 GPU) + MFMA util % of bf16 peak",
+        "value": value, "unit": "visual tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d layers, D=%d, %dx%d heads, MLP %d, patch %d, %d items, %d patch tokens -> %d visual tokens"
+                               % (cfg.name, L, D, cfg.num_heads, cfg.head_dim, F, cfg.patch, len(grids), T, Tm),
+                   "patch_tokens": T, "visual_tokens": Tm, "patch_tokens_per_s": T * args.steps / dt,
+                   "tflops_end_to_end": flops_call / (ms_per_step * 1e-3) / 1e12,
+                   "mfma_util_pct_end_to_end": 100 * flops_call / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches": dom_n, "avg_launch_ms": dom_ms / max(dom_n, 1),
+                     "flops_per_launch": dom_work / max(dom_n, 1)},
+        "cpu_baseline": cpu,
+        "steps_ms": {k: v[0] for k, v in table.items() if v[1] > 0},
+    }
+    enc.close()
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

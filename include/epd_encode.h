@@ -1,0 +1,182 @@
+/* epd_encode.h -- C ABI of the MI355X (gfx950) Encode-stage library.
+ *
+ * The Encode stage of an Encode / Prefill / Decode disaggregated multimodal server maps a
+ * multimodal input I_m to an embedding sequence V_m = E(I_m), V_m in R^{n x d}: n visual
+ * tokens, one d-dimensional row each (paper section 3.1 "Encode Stage", Eq. 1).  For images
+ * and video E is a Vision Transformer whose attention cost grows quadratically with the
+ * visual sequence length (paper section 1).  This library is that forward pass:
+ *
+ *   packed patch rows -> patch embedding -> L x [norm, QKV + rotary, block-diagonal
+ *   non-causal attention, output projection + residual, norm, GELU MLP + residual]
+ *   -> final norm -> merge x merge spatial gather -> projection -> V_m.
+ *
+ * Every step runs in hand-written HIP kernels on the caller's stream.  The library never
+ * allocates device memory: the caller provides one workspace (see
+ * epd_encode_workspace_bytes) that also receives a repacked copy of the weights.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device, "host" pointers are
+ *     ordinary process memory.  All matrices are dense row-major.
+ *   - Linear weights are W[out, in] with bias b[out]; y = x W^T + b.
+ *   - Status codes are returned, nothing aborts or throws across the ABI; a message for the
+ *     last failure is available from epd_encode_last_error.  After any error the handle
+ *     remains usable.
+ *   - Execution is asynchronous on `stream`; kernel faults surface at the caller's next
+ *     synchronisation.  One call at a time per handle (the workspace is shared).
+ *   - Results are deterministic: identical inputs give bit-identical outputs (no atomics,
+ *     no data-dependent reduction order), so a consumer that lost a feature can recompute
+ *     it (paper section 3.2, fault-tolerant recomputation) and obtain the same tensor.
+ */
+#ifndef EPD_ENCODE_H
+#define EPD_ENCODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct epd_encoder* epd_handle;
+
+typedef enum {
+  EPD_OK = 0,
+  EPD_ERR_INVALID_ARG = -1, /* NULL pointer, bad enum value, bad struct_size            */
+  EPD_ERR_UNSUPPORTED = -2, /* a shape the kernels do not cover (see epd_encode_create)  */
+  EPD_ERR_SHAPE = -3,       /* per-call metadata inconsistent or over the configured max  */
+  EPD_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small                 */
+  EPD_ERR_HIP = -5          /* a HIP runtime call failed (message has the HIP error)      */
+} epd_status;
+
+typedef enum { EPD_F32 = 0, EPD_BF16 = 1 } epd_dtype;
+typedef enum { EPD_LAYERNORM = 0, EPD_RMSNORM = 1 } epd_norm;
+typedef enum { EPD_GELU_ERF = 0, EPD_GELU_TANH = 1 } epd_act;
+typedef enum { EPD_ROPE_NONE = 0, EPD_ROPE_2D = 2, EPD_ROPE_3D = 3 } epd_rope;
+
+/* Per-layer tensors: DEVICE pointers, element type = cfg.dtype. */
+typedef struct {
+  const void* norm1_g; /* [D]                                                      */
+  const void* norm1_b; /* [D], NULL for RMSNorm                                    */
+  const void* qkv_w;   /* [3D, D]; rows: Q heads, then K heads, then V heads       */
+  const void* qkv_b;   /* [3D] or NULL when use_bias == 0                          */
+  const void* proj_w;  /* [D, D]                                                   */
+  const void* proj_b;  /* [D] or NULL                                              */
+  const void* norm2_g; /* [D]                                                      */
+  const void* norm2_b; /* [D], NULL for RMSNorm                                    */
+  const void* fc1_w;   /* [F, D]                                                   */
+  const void* fc1_b;   /* [F] or NULL                                              */
+  const void* fc2_w;   /* [D, F]                                                   */
+  const void* fc2_b;   /* [D] or NULL                                              */
+} epd_layer_weights;
+
+typedef struct {
+  const void* patch_w;             /* device [D, Pdim], Pdim = in_channels*temporal_patch*patch^2 */
+  const void* patch_b;             /* device [D] or NULL                                           */
+  const epd_layer_weights* layers; /* HOST array [num_layers] of device pointers                   */
+  const void* final_norm_g;        /* device [D] (ignored when final_norm == 0)                    */
+  const void* final_norm_b;        /* device [D], NULL for RMSNorm                                 */
+  const void* merge_w;             /* device [out_dim, merge*merge*D]                              */
+  const void* merge_b;             /* device [out_dim] or NULL                                     */
+} epd_weights;
+
+typedef struct {
+  uint32_t struct_size; /* sizeof(epd_encode_cfg) of the caller's header (ABI check)            */
+  int32_t dtype;        /* epd_dtype: storage type of weights, input patches and output.
+                           EPD_F32 computes in true fp32; EPD_BF16 multiplies in bf16 on the
+                           matrix cores with fp32 accumulation and an fp32 residual stream.    */
+  int32_t num_layers;   /* L >= 0                                                              */
+  int32_t hidden;       /* D = num_heads * head_dim                                            */
+  int32_t num_heads;    /* H                                                                   */
+  int32_t head_dim;     /* d, even; bf16: multiple of 8 and <= 128; fp32: <= 128               */
+  int32_t mlp_dim;      /* F                                                                   */
+  int32_t in_channels, patch, temporal_patch;
+  int32_t norm;         /* epd_norm                                                            */
+  float norm_eps;
+  int32_t act;          /* epd_act                                                             */
+  int32_t use_bias;     /* 1: every linear has a bias vector                                   */
+  int32_t rope;         /* epd_rope                                                            */
+  float rope_base;
+  int32_t rope_pairs[3]; /* rotary pairs of the (t, h, w) axes; sum = head_dim/2 unless
+                            rope == EPD_ROPE_NONE.  Pair p of a head is its elements
+                            (p, p + d/2); pairs go to the axes in the order t, h, w; the
+                            j-th pair of an axis with n pairs turns by coord * base^(-j/n). */
+  int32_t final_norm;   /* 1: norm before the merger                                           */
+  int32_t merge;        /* spatial merge size m (2; 1 = no gather)                             */
+  int32_t out_dim;      /* width of V_m                                                        */
+  int32_t max_tokens;   /* largest T (packed patch rows) of any call                           */
+  int32_t max_segments; /* largest number of attention segments of any call                    */
+  int32_t max_items;    /* largest number of images / clips of any call                        */
+  const epd_weights* weights; /* HOST struct of device pointers; read (copied into the
+                                 workspace in kernel-friendly order) during create, free to
+                                 release afterwards                                            */
+  void* workspace;      /* device, 256-byte aligned, >= epd_encode_workspace_bytes(cfg);
+                           owned by the caller, must outlive the handle                        */
+  uint64_t workspace_bytes;
+} epd_encode_cfg;
+
+/* Bytes of device workspace a handle for `cfg` needs (weights copy + activations + plan
+ * arrays).  Pure host arithmetic; only the shape fields of cfg are read.  Returns 0 when
+ * cfg is NULL or invalid. */
+uint64_t epd_encode_workspace_bytes(const epd_encode_cfg* cfg);
+
+/* Build an encoder E (Eq. 1).  Validates cfg (EPD_ERR_INVALID_ARG / EPD_ERR_UNSUPPORTED /
+ * EPD_ERR_WORKSPACE are decided on the host before any HIP call), copies and reorders the
+ * weights into the workspace on the null stream and waits for that copy.  *out is written
+ * only on success. */
+epd_status epd_encode_create(const epd_encode_cfg* cfg, epd_handle* out);
+
+/* V_m = E(I_m).
+ *   packed_patches    device [T, Pdim], cfg.dtype.  Items (images / clips) are packed in
+ *                     order; item (t, h, w) contributes t*h*w rows in raster order
+ *                     (ti*h + r)*w + c; a row holds (channel, temporal offset, row in
+ *                     patch, column in patch).
+ *   cu_seqlens        HOST int32 [num_segments + 1]: attention segment s is the token range
+ *                     [cu[s], cu[s+1]); cu[0] = 0, strictly increasing, cu[last] = T.
+ *                     A token attends to the tokens of its own segment only (non-causal).
+ *   grid_thw          HOST int32 [num_items, 3]: (t, h, w) in patch units; sum t*h*w = T;
+ *                     h and w divisible by cfg.merge.  Rotary coordinates are (ti, r, c)
+ *                     within the item.  Segments need not coincide with items.
+ *   out_visual_tokens device [sum t*(h/m)*(w/m), out_dim], cfg.dtype: merged token
+ *                     (ti, i, j) concatenates window rows then columns
+ *                     ((mi, mj), (mi, mj+1), ..., (mi+1, mj), ...) and is projected.
+ *   stream            hipStream_t (NULL = the null stream).
+ * Both host arrays are consumed before the call returns.  Inconsistent metadata returns
+ * EPD_ERR_SHAPE with nothing launched. */
+epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* cu_seqlens,
+                      int32_t num_segments, const int32_t* grid_thw, int32_t num_items,
+                      void* out_visual_tokens, void* stream);
+
+/* Release host-side state (events, pinned staging).  The workspace stays the caller's. */
+epd_status epd_encode_destroy(epd_handle h);
+
+/* Message of the last failure on this handle (or of the last failed create on this thread
+ * when h == NULL).  Never NULL; valid until the next call on the same handle / thread. */
+const char* epd_encode_last_error(epd_handle h);
+
+/* ---- measurement and test hooks (not needed to serve) --------------------------------- */
+
+/* Copy the fp32 residual stream [T, D] of the last epd_encode (the hidden state before the
+ * final norm) to a device buffer, asynchronously on `stream`. */
+epd_status epd_encode_debug_hidden(epd_handle h, void* out_T_by_D_f32, void* stream);
+
+/* Steps of the path, for per-kernel timing. */
+typedef enum {
+  EPD_STEP_PLAN = 0, EPD_STEP_PATCH_EMBED = 1, EPD_STEP_NORM = 2, EPD_STEP_QKV = 3,
+  EPD_STEP_ATTN = 4, EPD_STEP_PROJ = 5, EPD_STEP_FC1 = 6, EPD_STEP_FC2 = 7,
+  EPD_STEP_MERGE = 8, EPD_STEP_COUNT = 9
+} epd_step;
+
+/* Bracket every launch of `step` (an epd_step, or -1 to switch timing off) with HIP events
+ * on the stream it is launched on, in all following epd_encode calls. */
+epd_status epd_encode_set_timing(epd_handle h, int32_t step);
+
+/* Wait for the recorded events, return the summed kernel time and launch count since the
+ * last call of this function, and clear them.  Also returns the algorithmic work of those
+ * launches (flops for matrix steps, bytes moved for the norm step). */
+epd_status epd_encode_get_timing(epd_handle h, double* total_ms, int64_t* launches,
+                                 double* work);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EPD_ENCODE_H */

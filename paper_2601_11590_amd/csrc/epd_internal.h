@@ -1,0 +1,98 @@
+// Internal declarations shared by the C-ABI layer and the kernel files of the Encode-stage
+// library (V_m = E(I_m), paper section 3.1, Eq. 1).  Not installed; the public interface is
+// include/epd_encode.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace epd {
+
+// ---------------------------------------------------------------- GEMM description
+// C[M,N] = A[M,K] * W[N,K]^T (+ bias[N]) followed by one of the epilogues below.
+enum Epilogue : int {
+  EPI_STORE = 0,     // out[m][n] = acc + bias               (out dtype: see out_f32)
+  EPI_GELU = 1,      // out[m][n] = act(acc + bias)
+  EPI_RESIDUAL = 2,  // resid[m][n] += acc + bias            (fp32 residual stream, in place)
+  EPI_QKV = 3        // columns < qk_cols: rotate adjacent pairs by rot[m][.], store to out;
+                     // columns >= qk_cols: V.  fp32 path stores V to out as well; the bf16
+                     // path stores V transposed into vt[(n - qk_cols)][vcol[m]].
+};
+
+struct GemmArgs {
+  const void* A;        // [M, K] row-major, leading dimension lda (elements)
+  int lda;
+  const int32_t* gather;  // optional [M, gather_n]: row m of A is the concatenation of rows
+  int gather_n;           //   gather[m][0..gather_n) of A, each K/gather_n wide
+  const void* W;        // [N, K] row-major
+  const void* bias;     // [N] or nullptr
+  int M, N, K;
+  int epilogue;         // Epilogue
+  int act;              // 0 = GELU erf, 1 = GELU tanh (EPI_GELU)
+  void* out;            // [M, ldo]
+  int ldo;
+  int out_f32;          // bf16 path only: 1 = out is fp32 (patch embed writes the residual stream)
+  float* resid;         // [M, ldr] (EPI_RESIDUAL)
+  int ldr;
+  // EPI_QKV
+  const float2* rot;    // [M, rot_pairs] (cos, sin); nullptr = no rotary
+  int rot_pairs;        // head_dim / 2
+  int head_dim;
+  int qk_cols;          // 2 * hidden
+  void* vt;             // bf16 [hidden, vt_stride] transposed V
+  int vt_stride;
+  const int32_t* vcol;  // [M] column of token m in vt
+};
+
+// ---------------------------------------------------------------- attention description
+// One work item = one tile of query rows of one segment (all heads via gridDim.y).
+struct AttnWork { int32_t q0, seg_start, seg_len, vcol0; };
+
+struct AttnArgs {
+  const void* qkv;      // fp32 path: [T, 3D] (Q | K | V); bf16 path: [T, 2D] (Q | K)
+  int ld_qkv;
+  const void* vt;       // bf16 path: [D, vt_stride]
+  int vt_stride;
+  void* out;            // [T, D]
+  int ld_out;
+  const AttnWork* work;
+  int num_work;
+  int num_heads, head_dim;
+  float scale;          // 1 / sqrt(head_dim)
+};
+
+// ---------------------------------------------------------------- plan (per-call metadata)
+struct PlanArgs {
+  int T, Tm, num_items, num_segments;
+  const int32_t* item_tok_off;  // device [items + 1]
+  const int32_t* item_mrg_off;  // device [items + 1]
+  const int32_t* grid_thw;      // device [items, 3]
+  const int32_t* cu;            // device [segments + 1]
+  const int32_t* pcu;           // device [segments + 1] padded segment starts in vt
+  const double* pair_freq;      // device [pairs]
+  const int32_t* pair_axis;     // device [pairs]
+  int pairs;                    // 0 = no rotary
+  int merge;
+  float2* rot;                  // out [T, pairs]
+  int32_t* merge_idx;           // out [Tm, merge*merge]
+  int32_t* vcol;                // out [T] or nullptr
+  void* vt;                     // bf16 [D, vt_stride]: pad columns are cleared, or nullptr
+  int vt_stride, hidden;
+};
+
+// launchers (each checks nothing: shapes are validated by the caller); all asynchronous
+void launch_plan(const PlanArgs& p, hipStream_t s);
+void launch_norm(const float* x, const void* gamma, const void* beta, void* out, int T, int D,
+                 float eps, bool rms, bool bf16, hipStream_t s);
+void launch_gemm_f32(const GemmArgs& g, hipStream_t s);
+bool launch_attn_f32(const AttnArgs& a, hipStream_t s);   // false: head_dim not covered
+void launch_gemm_bf16(const GemmArgs& g, hipStream_t s);
+bool launch_attn_bf16(const AttnArgs& a, hipStream_t s);  // false: head_dim not covered
+int attn_q_tile(bool bf16, int head_dim);                 // query rows per work item
+// dst[(sec, h, 2p+e)] = src[(sec, h, p + e*pairs)] for the Q and K sections, V copied
+void launch_permute_qkv(const void* src_w, const void* src_b, void* dst_w, void* dst_b,
+                        int hidden, int num_heads, int head_dim, int elem_bytes, hipStream_t s);
+
+constexpr int kVtAlign = 128;   // segment starts in the transposed-V buffer are multiples of this
+
+}  // namespace epd

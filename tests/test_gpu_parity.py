@@ -1,0 +1,91 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded
+inputs, element by element, at sizes the oracle finishes in seconds and that still span
+several tiles with ragged tails.  Tolerances: fp32 max abs <= 1e-4; bf16 per-token cosine
+>= 0.999 and per-token max-norm relative error <= 2e-2."""
+
+import numpy as np
+import pytest
+
+from oracle import vit_encode as O
+from paper_2601_11590_amd import workloads as W
+from parity_util import check, log, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def case(cfg, grids, segments="item", q_gain=1.0, std=0.02):
+    gw = W.global_weights(cfg, std)
+    layers = [W.layer_weights(cfg, l, std, q_gain) for l in range(cfg.num_layers)]
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids, segments)
+    return gw, layers, patches, cu, grid
+
+
+def parity(cfg, grids, **kw):
+    log("case %s dtype=%s L=%d D=%d d=%d F=%d grids=%s %s" % (cfg.name, cfg.dtype, cfg.num_layers, cfg.hidden,
+                                                              cfg.head_dim, cfg.mlp_dim, grids[:6], kw))
+    gw, layers, patches, cu, grid = case(cfg, grids, **kw)
+    ref, ref_h = O.encode(cfg, gw, layers, patches, cu, grid, return_hidden=True)
+    got, got_h = run_gpu(cfg, gw, layers, patches, cu, grid, want_hidden=True)
+    assert got.shape == ref.shape
+    check(cfg, got_h, ref_h, "hidden")
+    return check(cfg, got, ref, "output")
+
+
+def small(dtype, **kw):
+    base = dict(name="small-" + dtype, dtype=dtype, num_layers=2, hidden=256, num_heads=4, head_dim=64,
+                mlp_dim=512, patch=4, temporal_patch=1, norm="rmsnorm", rope="2d", rope_pairs=(0, 16, 16),
+                out_dim=192, seed=11)
+    base.update(kw)
+    return W.EncoderConfig(**base)
+
+
+RAGGED = [(1, 6, 10), (1, 2, 2), (1, 14, 18), (2, 4, 4), (1, 2, 38)]     # 60 + 4 + 252 + 32 + 76 tokens
+
+
+def test_c1_fp32_full_config():
+    parity(W.C1, W.grids_for(W.C1))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),
+    dict(norm="layernorm", rope="3d", rope_pairs=(8, 12, 12), act="gelu_tanh"),
+    dict(num_heads=2, head_dim=72, hidden=144, rope_pairs=(0, 18, 18), norm="layernorm"),
+    dict(num_heads=2, head_dim=128, rope="3d", rope_pairs=(16, 24, 24)),
+    dict(rope="none", rope_pairs=(0, 0, 0), use_bias=False),
+    dict(num_layers=0),
+], ids=["rms2d", "ln3d-tanh", "d72", "d128-3d", "norope-nobias", "L0"])
+def test_fp32_small_ragged(kw):
+    parity(small("f32", **kw), RAGGED)
+
+
+def test_fp32_frame_segments_and_sharp_softmax():
+    parity(small("f32"), [(3, 4, 6), (1, 2, 2)], segments="frame")
+    parity(small("f32"), RAGGED, q_gain=16.0, std=0.05)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(),
+    dict(norm="layernorm", rope="3d", rope_pairs=(8, 12, 12), act="gelu_tanh"),
+    dict(num_heads=2, head_dim=72, hidden=144, mlp_dim=304, rope_pairs=(0, 18, 18), norm="layernorm", out_dim=200),
+    dict(num_heads=2, head_dim=128, rope="3d", rope_pairs=(16, 24, 24), patch=2, temporal_patch=2),
+    dict(rope="none", rope_pairs=(0, 0, 0), use_bias=False),
+    dict(num_layers=0),
+], ids=["rms2d", "ln3d-tanh", "d72", "d128-3d", "norope-nobias", "L0"])
+def test_bf16_small_ragged(kw):
+    parity(small("bf16", **kw), RAGGED)
+
+
+def test_bf16_frame_segments_and_sharp_softmax():
+    parity(small("bf16"), [(3, 4, 6), (1, 2, 2)], segments="frame")
+    parity(small("bf16"), RAGGED, q_gain=16.0, std=0.05)
+
+
+def test_bf16_many_tiles():
+    # > 2 row tiles of every GEMM, attention segments with several query and key tiles
+    parity(small("bf16", num_layers=3), [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8)])
+
+
+def test_c2_width_two_layers_full_batch():
+    cfg = W.C2.replace(num_layers=2)
+    parity(cfg, W.grids_for(W.C2))
