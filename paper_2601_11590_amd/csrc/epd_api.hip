@@ -44,7 +44,7 @@ struct Layout {
   int pdim, pairs, mm, max_tm, max_work, vt_stride;
   size_t patch_w, patch_b, final_g, final_b, merge_w, merge_b;
   std::vector<LayerW> layers;
-  size_t x, xn, qkv, vt, o, hd, rot, merge_idx, vcol, pair_freq, pair_axis, meta;
+  size_t x, xn, qkv, vt, o, hd, rot, merge_idx, vcol, pair_freq, pair_axis, zeros, meta;
   size_t meta_bytes, total;
 };
 
@@ -104,6 +104,7 @@ Layout make_layout(const epd_encode_cfg& c) {
   L.vcol = take(T * 4, bf);
   L.pair_freq = take((size_t)std::max(L.pairs, 1) * 8);
   L.pair_axis = take((size_t)std::max(L.pairs, 1) * 4);
+  L.zeros = take(256);
   const size_t S = c.max_segments, I = c.max_items;
   L.meta_bytes = align_up(((S + 1) * 2 + (I + 1) * 2 + 3 * I + 4 * (size_t)L.max_work) * 4);
   L.meta = take(L.meta_bytes);
@@ -318,7 +319,9 @@ epd_status epd_encode_create(const epd_encode_cfg* cfg, epd_handle* out) {
     if (e == hipSuccess) e = hipMemcpy(h->ws + L.pair_axis, axis.data(), L.pairs * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) { h->err = fmt("rotary table upload failed: %s", hipGetErrorString(e)); return fail(EPD_ERR_HIP); }
   }
-  hipError_t e = hipHostMalloc((void**)&h->staging, L.meta_bytes * kStagingSlots, hipHostMallocDefault);
+  hipError_t e = hipMemsetAsync(h->ws + L.zeros, 0, 256, 0);
+  if (e != hipSuccess) { h->err = fmt("hipMemsetAsync failed: %s", hipGetErrorString(e)); return fail(EPD_ERR_HIP); }
+  e = hipHostMalloc((void**)&h->staging, L.meta_bytes * kStagingSlots, hipHostMallocDefault);
   if (e != hipSuccess) { h->staging = nullptr; h->err = fmt("hipHostMalloc failed: %s", hipGetErrorString(e)); return fail(EPD_ERR_HIP); }
   for (auto& ev : h->slot_done) {
     e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
@@ -437,6 +440,7 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
 
   auto gemm = [&](int step, GemmArgs& g) {
     StepTimer tm(h, step, 2.0 * g.M * (double)g.N * g.K, st);
+    g.zeros = h->ws + L.zeros;
     if (bf) launch_gemm_bf16(g, st); else launch_gemm_f32(g, st);
   };
   auto norm = [&](const void* gma, const void* bta, void* dst) {

@@ -42,6 +42,8 @@ struct GemmArgs {
   void* vt;             // bf16 [hidden, vt_stride] transposed V
   int vt_stride;
   const int32_t* vcol;  // [M] column of token m in vt
+  const void* zeros;    // bf16 path: >= 16 readable zero bytes (source of out-of-range tile chunks)
+  int tile_cfg;         // bf16 path: 0 = automatic choice, k > 0 = tile variant k - 1 (tuning)
 };
 
 // ---------------------------------------------------------------- attention description

@@ -2,15 +2,17 @@
 // patch embedding, QKV projection with rotary epilogue, attention output projection, the
 // two MLP GEMMs and the merger projection all are  C[M,N] = A[M,K] * W[N,K]^T (+bias)  with
 // different epilogues.  Written for gfx950: 64-lane waves, v_mfma_f32_32x32x16_bf16 (fp32
-// accumulate), operand tiles staged through LDS with 16-byte accesses.
+// accumulate), operand tiles brought from global memory straight into LDS
+// (global_load_lds_dwordx4, no register staging) in a multi-stage ring.
 //
 // Tile scheme.  A block of WAVES_M x WAVES_N waves owns a BM x BN output tile; K advances in
-// steps of 64.  Both operands are K-contiguous in memory ("NT" form), so one lane's MFMA
-// operand (8 consecutive k of one row) is one 16-byte LDS read; LDS rows are padded by 16
-// bytes so the 32 rows read by one instruction fall in distinct bank groups.  The next K
-// tile is fetched from global memory into registers while the current one is multiplied;
-// blocks are sized so two fit on a compute unit and fill each other's barrier and epilogue
-// gaps.
+// steps of BK.  Both operands are K-contiguous in memory ("NT" form), so one lane's MFMA
+// operand (8 consecutive k of one row) is one 16-byte LDS read.  A direct-to-LDS load writes
+// the 64 lanes' 16-byte chunks to consecutive LDS addresses, so rows cannot be padded;
+// instead the chunk a lane fetches is chosen so that chunk c of row r lands in slot
+// c ^ swz(r) of that row, which spreads the 32 rows read by one MFMA operand fetch over all
+// bank groups.  Stage s+STAGES-1 is in flight while stage s is multiplied; one barrier per
+// K step.
 //
 // Accumulator orientation.  For a 32x32 MFMA result lane l holds column (l % 32) and rows
 // 8*(v/4) + 4*(l/32) + (v%4), v = 0..15.  By default the W fragment is fed as the first
@@ -22,15 +24,17 @@
 // attention kernel's second GEMM.
 #include "epd_internal.h"
 
+#include <cstdlib>
+#include <type_traits>
+
 namespace epd {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int BK = 64;
-constexpr int LDK = BK + 8;   // LDS row stride in elements (144 bytes)
+#define EPD_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define EPD_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 __device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d) {
   bf16x2 lo, hi;
@@ -42,21 +46,20 @@ __device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d)
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
-// Gaussian CDF through the complementary error function, rational-exponential form of the
-// Handbook of Mathematical Functions, 7.1.26 (absolute error of erf below 1.5e-7, far below
-// the bf16 rounding of the result).
+// x * Phi(x) with the Gaussian CDF through the complementary error function in the
+// rational-exponential form of the Handbook of Mathematical Functions, 7.1.26 (absolute
+// error of erf below 1.5e-7, far below the bf16 rounding of the result):
+//   h = erfc(|x|/sqrt2) / 2,   gelu(x) = max(x, 0) - |x| h.
 __device__ __forceinline__ float gelu_erf_fast(float x) {
-  const float z = fabsf(x) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, ax, 1.0f));
+  float p = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+  p = fmaf(p, t, 0.5f * 1.421413741f);
+  p = fmaf(p, t, 0.5f * -0.284496736f);
+  p = fmaf(p, t, 0.5f * 0.254829592f);
   p *= t;
-  const float e = __builtin_amdgcn_exp2f(-z * z * 1.44269504088896340736f);
-  const float half_erfc = 0.5f * p * e;                 // 0.5 * erfc(|x| / sqrt 2)
-  const float cdf = x < 0.f ? half_erfc : 1.0f - half_erfc;
-  return x * cdf;
+  const float e = __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.44269504088896340736f));
+  return fmaf(-ax, p * e, fmaxf(x, 0.f));
 }
 
 __device__ __forceinline__ float gelu_tanh_fast(float x) {
@@ -67,83 +70,122 @@ __device__ __forceinline__ float gelu_tanh_fast(float x) {
 
 enum OutKind : int { OUT_BF16 = 0, OUT_F32 = 1 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int OUT, bool VMODE, bool GATHER>
-__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const int n0, __bf16* lds) {
-  constexpr int NT = 64 * WAVES_M * WAVES_N;
-  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-  constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int CPT_A = BM * (BK / 8) / NT, CPT_W = BN * (BK / 8) / NT;
-  static_assert(BM * (BK / 8) % NT == 0 && BN * (BK / 8) % NT == 0, "tile / thread mismatch");
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
-  __bf16* As = lds;
-  __bf16* Ws = lds + BM * LDK;
+// Explicit LDS reads and counter waits (see the main loop of gemm_tile for why).
+template <int OFF> __device__ __forceinline__ void ds_read_b128(bf16x8& d, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int N, int STRIDE, int I = 0> __device__ __forceinline__ void ds_read_rows(bf16x8* d, uint32_t addr) {
+  if constexpr (I < N) {
+    ds_read_b128<I * STRIDE>(d[I], addr);
+    ds_read_rows<N, STRIDE, I + 1>(d, addr);
+  }
+}
+// wait until at most PENDING LDS reads of this wave are outstanding (they return in order),
+// then tie the N fragments to the wait so that their consumers cannot be scheduled above it
+template <int PENDING, int N> __device__ __forceinline__ void wait_lds_reads(bf16x8* f) {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(PENDING) : "memory");
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
+}
+
+// Compile-time description of one kernel variant.
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int MINBLK_>
+struct Tile {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int MINBLK = MINBLK_;
+  static constexpr int NT = 64 * WAVES_M * WAVES_N;
+  static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
+  static constexpr int CPR = BK / 8;                     // 16-byte chunks per tile row
+  static constexpr int LA = BM * CPR / NT, LW = BN * CPR / NT;   // load instructions per thread and stage
+  static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+  static constexpr int EPI_BYTES_A = BM * (BN / 2 * 4 + 16), EPI_BYTES_V = (BN / 2) * (BM * 4 + 16);
+  static constexpr int LDS_BYTES = (2 * STAGE_BYTES > EPI_BYTES_A ? 2 * STAGE_BYTES : EPI_BYTES_A) > EPI_BYTES_V
+                                       ? (2 * STAGE_BYTES > EPI_BYTES_A ? 2 * STAGE_BYTES : EPI_BYTES_A) : EPI_BYTES_V;
+  static_assert(BK == 32 || BK == 64, "BK");
+  static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0, "tile / thread mismatch");
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+  // LDS has 64 banks of 4 bytes: a 16-byte-per-lane read is served 16 lanes (256 bytes) at a
+  // time, so 16 consecutive rows must map to 16 different 16-byte columns modulo 256 bytes.
+  __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+};
+
+template <class T, int EPI, int OUT, bool VMODE, bool GATHER>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const int n0, char* const lds) {
+  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, WM = T::WM, WN = T::WN, TM = T::TM, TN = T::TN;
+  constexpr int CPR = T::CPR, LA = T::LA, LW = T::LW;
+  constexpr int ROWB = BK * 2;               // bytes per tile row
+  constexpr int A_BYTES = BM * ROWB;
+
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS bases scalar
+  const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
   const int l32 = lane & 31, lg = lane >> 5;
 
-  const __bf16* A = (const __bf16*)g.A;
-  const __bf16* W = (const __bf16*)g.W;
+  const char* zeros = (const char*)g.zeros;
   const int kcw = GATHER ? g.K / g.gather_n : g.K;
 
-  // per-thread chunk descriptors: chunk c = p * NT + tid -> row c / 8, k chunk c % 8
-  const __bf16* a_src[CPT_A];
-  bool a_ok[CPT_A];
-  int a_m[CPT_A];
+  // ---- per-thread load descriptors.  Load instruction `it` of a stage covers LDS chunks
+  // it*NT + wave*64 + lane; chunk c is row c / CPR, slot c % CPR, and holds k-chunk
+  // slot ^ swz(row) of that row.  Rows beyond M (or N) are clamped to the last valid row:
+  // they only feed accumulators that are never stored.  Addresses are a block-uniform base
+  // (advanced once per K step) plus a loop-invariant 32-bit per-lane byte offset.
+  const char* a_base_ptr = (const char*)g.A + (size_t)m0 * g.lda * 2;
+  const char* w_base_ptr = (const char*)g.W + (size_t)n0 * g.K * 2;
+  uint32_t a_off[LA], w_off[LW];
+  int a_col[LA], w_col[LW], a_row[LA];
 #pragma unroll
-  for (int p = 0; p < CPT_A; ++p) {
-    const int c = p * NT + tid, row = c >> 3, kc = c & 7;
-    const int m = m0 + row;
-    a_ok[p] = m < g.M;
-    a_m[p] = m;
-    a_src[p] = A + (size_t)(a_ok[p] ? m : 0) * g.lda + kc * 8;
+  for (int it = 0; it < LA; ++it) {
+    const int c = it * NT + tid, row = c / CPR, col = (c % CPR) ^ T::swz(row);
+    const int r = min(row, g.M - 1 - m0);
+    a_col[it] = col * 8;
+    a_row[it] = m0 + r;
+    a_off[it] = (uint32_t)r * (uint32_t)g.lda * 2u + col * 16;
   }
-  const __bf16* w_src[CPT_W];
-  bool w_ok[CPT_W];
 #pragma unroll
-  for (int p = 0; p < CPT_W; ++p) {
-    const int c = p * NT + tid, row = c >> 3, kc = c & 7;
-    const int n = n0 + row;
-    w_ok[p] = n < g.N;
-    w_src[p] = W + (size_t)(w_ok[p] ? n : 0) * g.K + kc * 8;
+  for (int it = 0; it < LW; ++it) {
+    const int c = it * NT + tid, row = c / CPR, col = (c % CPR) ^ T::swz(row);
+    const int r = min(row, g.N - 1 - n0);
+    w_col[it] = col * 8;
+    w_off[it] = (uint32_t)r * (uint32_t)g.K * 2u + col * 16;
   }
 
-  uint4 a_reg[CPT_A], w_reg[CPT_W];
-  auto fetch = [&](int k0) {
+  // TAIL = the K step that may run past K (only the last one, only when K % BK != 0):
+  // chunks at k >= K are fetched from a zero buffer instead.
+  auto issue = [&](auto TAIL, char* st, int k0) {
+    constexpr bool tail = decltype(TAIL)::value;
+    const char* ab = a_base_ptr + (size_t)k0 * 2;
+    const char* wb = w_base_ptr + (size_t)k0 * 2;
 #pragma unroll
-    for (int p = 0; p < CPT_A; ++p) {
-      const int k = k0 + ((p * NT + tid) & 7) * 8;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (a_ok[p] && k < g.K) {
-        if constexpr (GATHER) {
-          const int piece = k / kcw;
-          const int src = g.gather[(size_t)a_m[p] * g.gather_n + piece];
-          v = *(const uint4*)(A + (size_t)src * g.lda + (k - piece * kcw));
-        } else {
-          v = *(const uint4*)(a_src[p] + k0);
-        }
+    for (int it = 0; it < LA; ++it) {
+      const char* p;
+      if constexpr (GATHER) {
+        const int k = k0 + a_col[it];
+        const int piece = min(k / kcw, g.gather_n - 1);
+        const int src = g.gather[(size_t)a_row[it] * g.gather_n + piece];
+        p = (const char*)g.A + ((size_t)src * g.lda + (k - piece * kcw)) * 2;
+      } else {
+        p = ab + a_off[it];
       }
-      a_reg[p] = v;
+      if constexpr (tail) { if (k0 + a_col[it] >= g.K) p = zeros; }
+      __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(st + (it * NT + wave * 64) * 16), 16, 0, 0);
     }
 #pragma unroll
-    for (int p = 0; p < CPT_W; ++p) {
-      const int k = k0 + ((p * NT + tid) & 7) * 8;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (w_ok[p] && k < g.K) v = *(const uint4*)(w_src[p] + k0);
-      w_reg[p] = v;
+    for (int it = 0; it < LW; ++it) {
+      const char* p = wb + w_off[it];
+      if constexpr (tail) { if (k0 + w_col[it] >= g.K) p = zeros; }
+      __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(st + A_BYTES + (it * NT + wave * 64) * 16), 16, 0, 0);
     }
   };
-  auto stash = [&]() {
-#pragma unroll
-    for (int p = 0; p < CPT_A; ++p) {
-      const int c = p * NT + tid;
-      *(uint4*)(As + (c >> 3) * LDK + (c & 7) * 8) = a_reg[p];
-    }
-#pragma unroll
-    for (int p = 0; p < CPT_W; ++p) {
-      const int c = p * NT + tid;
-      *(uint4*)(Ws + (c >> 3) * LDK + (c & 7) * 8) = w_reg[p];
-    }
+  const int nk = (g.K + BK - 1) / BK;
+  const bool ragged_k = (g.K % BK) != 0;
+  auto issue_step = [&](char* st, int kt) {      // kt < nk
+    if (ragged_k && kt == nk - 1) issue(std::true_type{}, st, kt * BK);
+    else issue(std::false_type{}, st, kt * BK);
   };
 
   f32x16 acc[TM][TN];
@@ -154,111 +196,208 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const __bf16* a_rd = As + (wm * WM + l32) * LDK + lg * 8;
-  const __bf16* w_rd = Ws + (wn * WN + l32) * LDK + lg * 8;
-
-  const int nk = (g.K + BK - 1) / BK;
-  fetch(0);
-  for (int kt = 0; kt < nk; ++kt) {
-    __syncthreads();
-    stash();
-    __syncthreads();
-    if (kt + 1 < nk) fetch((kt + 1) * BK);
+  // ---- LDS fragment reads.  Issued as explicit ds_read_b128 so that their order against the
+  // direct-to-LDS loads and the waits below is exactly the one written here (a compiler-
+  // visible LDS read that follows a direct-to-LDS load in program order gets a full wait for
+  // that load inserted in front of it, which would serialise the two-stage ring).
+  // Row of lane = wave row + i*32 + l32; multiples of 32 keep swz(row) = swz(l32).
+  constexpr int KS = BK / 16, NF = TM + TN;
+  const uint32_t lds0 = (uint32_t)(size_t)EPD_LPTR(lds);
+  uint32_t a_rd[2][KS], w_rd[2][KS];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[TM], wf[TN];
+  for (int st = 0; st < 2; ++st)
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *(const bf16x8*)(a_rd + i * 32 * LDK + ks * 16);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) wf[j] = *(const bf16x8*)(w_rd + j * 32 * LDK + ks * 16);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          if constexpr (VMODE)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
-          else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
-        }
+    for (int ks = 0; ks < KS; ++ks) {
+      const int off = ((ks * 2 + lg) ^ T::swz(l32)) * 16;
+      a_rd[st][ks] = lds0 + st * T::STAGE_BYTES + (wm * WM + l32) * ROWB + off;
+      w_rd[st][ks] = lds0 + st * T::STAGE_BYTES + A_BYTES + (wn * WN + l32) * ROWB + off;
     }
+  bf16x8 frag[2][NF];
+  auto read_frags = [&](auto BUF, auto ST, auto KSTEP) {
+    constexpr int buf = decltype(BUF)::value, st = decltype(ST)::value, ks = decltype(KSTEP)::value;
+    ds_read_rows<TM, 32 * ROWB>(&frag[buf][0], a_rd[st][ks]);
+    ds_read_rows<TN, 32 * ROWB>(&frag[buf][TM], w_rd[st][ks]);
+  };
+  auto wait_frags = [&](auto BUF, auto PENDING) {
+    wait_lds_reads<decltype(PENDING)::value, NF>(&frag[decltype(BUF)::value][0]);
+  };
+  auto mfmas = [&](auto BUF) {
+    constexpr int buf = decltype(BUF)::value;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if constexpr (VMODE)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[buf][i], frag[buf][TM + j], acc[i][j], 0, 0, 0);
+        else
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[buf][TM + j], frag[buf][i], acc[i][j], 0, 0, 0);
+      }
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+
+  // ---- main loop: two LDS stages.  The hand-over to the next stage happens before the last
+  // 16-wide k slice of the current stage is multiplied: wait for the own loads of stage s^1,
+  // barrier (everybody's loads landed, everybody finished reading stage s), refill stage s
+  // with K step kt+2, start reading stage s^1 -- and only then issue the MFMAs of the last
+  // slice, which cover the barrier and the LDS latency.  Every load has one full K step to land.
+  issue_step(lds, 0);
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+  if (nk > 1 && !(g.tile_cfg & 256)) issue_step(lds + T::STAGE_BYTES, 1);
+  read_frags(I0{}, I0{}, I0{});
+
+  auto step = [&](auto S, int kt) {
+    constexpr int s = decltype(S)::value;
+    using SN = std::integral_constant<int, s ^ 1>;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks < KS - 1) {
+        // fragments of slice ks+1 are requested before slice ks is multiplied
+        if (ks & 1) { if (ks == 1) read_frags(I0{}, S, std::integral_constant<int, (2 < KS ? 2 : 0)>{}); }
+        else { if (ks == 0) read_frags(I1{}, S, I1{}); else read_frags(I1{}, S, std::integral_constant<int, (3 < KS ? 3 : 1)>{}); }
+        if (ks & 1) { wait_frags(I1{}, std::integral_constant<int, NF>{}); mfmas(I1{}); }
+        else { wait_frags(I0{}, std::integral_constant<int, NF>{}); mfmas(I0{}); }
+      } else {
+        // last slice (fragment buffer 1): stage hand-over first
+        if (kt + 1 < nk) {
+          wait_vmcnt<0>();
+          wait_frags(I1{}, I0{});
+          if (!(g.tile_cfg & 512)) __builtin_amdgcn_s_barrier();
+          if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(lds + s * T::STAGE_BYTES, kt + 2);
+          read_frags(I0{}, SN{}, I0{});
+        } else {
+          wait_frags(I1{}, I0{});
+        }
+        mfmas(I1{});
+      }
+    }
+  };
+  for (int kt = 0; kt < nk; kt += 2) {
+    step(I0{}, kt);
+    if (kt + 1 < nk) step(I1{}, kt + 1);
   }
 
   // ------------------------------------------------------------------ epilogue
+  // The accumulators go through LDS (the operand stages are dead by now) so that global
+  // memory sees row-contiguous accesses: straight from the MFMA layout every store
+  // instruction would touch 32 different rows with 16 bytes each.  Two passes, each staging
+  // one half of the tile's columns as fp32 (BM rows x BN/2 floats, rows padded by 16 bytes);
+  // then every group of 32 lanes owns one row and a lane owns 4 consecutive columns, which is
+  // where bias, activation, rotary and the residual add are applied.
+  constexpr int HALF = BN / 2;
+  constexpr int WPH = T::WAVES_N / 2;                 // wave columns per half
+  static_assert(T::WAVES_N % 2 == 0 && HALF % 32 == 0, "epilogue halves");
   const uint16_t* bias = (const uint16_t*)g.bias;
+  wait_vmcnt<0>();
   if constexpr (VMODE) {
-    // lane: column n, runs of 4 consecutive tokens
+    // staged transposed: ET[channel][token], so that a lane ends up with consecutive tokens
+    constexpr int ROWE = BM * 4 + 16;
     uint16_t* vt = (uint16_t*)g.vt;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * WN + j * 32 + l32;
-      if (n >= g.N) continue;
-      const float b = bias ? bf16_bits_to_float(bias[n]) : 0.f;
-      uint16_t* vrow = vt + (size_t)(n - g.qk_cols) * g.vt_stride;
+    for (int h = 0; h < 2; ++h) {
+      __syncthreads();
+      if (wn / WPH == h) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j) {
+          const int ch = (wn % WPH) * WN + j * 32 + l32;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int m = m0 + wm * WM + i * 32 + q * 8 + lg * 4;
-          if (m >= g.M) continue;
-          const uint2 pk = pack_bf16x4(acc[i][j][4 * q] + b, acc[i][j][4 * q + 1] + b,
-                                       acc[i][j][4 * q + 2] + b, acc[i][j][4 * q + 3] + b);
-          if (m + 3 < g.M) {
-            const int4 vc = *(const int4*)(g.vcol + m);
-            if (vc.w - vc.x == 3) {
-              *(uint2*)(vrow + vc.x) = pk;
-            } else {
-              vrow[vc.x] = (uint16_t)(pk.x & 0xffff); vrow[vc.y] = (uint16_t)(pk.x >> 16);
-              vrow[vc.z] = (uint16_t)(pk.y & 0xffff); vrow[vc.w] = (uint16_t)(pk.y >> 16);
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int ml = wm * WM + i * 32 + q * 8 + lg * 4;
+              *(float4*)(lds + ch * ROWE + ml * 4) =
+                  make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
             }
-          } else {
-            const uint16_t e[4] = {(uint16_t)(pk.x & 0xffff), (uint16_t)(pk.x >> 16),
-                                   (uint16_t)(pk.y & 0xffff), (uint16_t)(pk.y >> 16)};
-            for (int t = 0; t < 4 && m + t < g.M; ++t) vrow[g.vcol[m + t]] = e[t];
-          }
         }
+      }
+      __syncthreads();
+      // BM tokens per channel row: BM/8 lanes per row, 8 tokens (one 16-byte bf16 store) per lane
+      constexpr int LPRV = BM / 8, RPS = NT / LPRV;
+      const int tl = (tid % LPRV) * 8;
+      const int m = m0 + tl;
+      int4 vc0 = make_int4(0, 0, 0, 0), vc1 = make_int4(0, 0, 0, 0);
+      const bool full = m + 7 < g.M;
+      if (full) { vc0 = *(const int4*)(g.vcol + m); vc1 = *(const int4*)(g.vcol + m + 4); }
+      const bool fast = full && (vc1.w - vc0.x == 7) && ((vc0.x & 7) == 0);
+      for (int r = tid / LPRV; r < HALF; r += RPS) {
+        const int n = n0 + h * HALF + r;
+        if (n >= g.N || m >= g.M) continue;
+        const float bv = bias ? bf16_bits_to_float(bias[n]) : 0.f;
+        const float4 e0 = *(const float4*)(lds + r * ROWE + tl * 4);
+        const float4 e1 = *(const float4*)(lds + r * ROWE + tl * 4 + 16);
+        const uint2 p0 = pack_bf16x4(e0.x + bv, e0.y + bv, e0.z + bv, e0.w + bv);
+        const uint2 p1 = pack_bf16x4(e1.x + bv, e1.y + bv, e1.z + bv, e1.w + bv);
+        uint16_t* vrow = vt + (size_t)(n - g.qk_cols) * g.vt_stride;
+        if (fast) {
+          *(uint4*)(vrow + vc0.x) = make_uint4(p0.x, p0.y, p1.x, p1.y);
+        } else {
+          const uint16_t e[8] = {(uint16_t)(p0.x & 0xffff), (uint16_t)(p0.x >> 16), (uint16_t)(p0.y & 0xffff), (uint16_t)(p0.y >> 16),
+                                 (uint16_t)(p1.x & 0xffff), (uint16_t)(p1.x >> 16), (uint16_t)(p1.y & 0xffff), (uint16_t)(p1.y >> 16)};
+          for (int t = 0; t < 8 && m + t < g.M; ++t) vrow[g.vcol[m + t]] = e[t];
+        }
+      }
     }
   } else {
-    // lane: token m, runs of 4 consecutive columns n
+    constexpr int ROWE = HALF * 4 + 16;
+    constexpr int LPR4 = HALF / 4, RPS = NT / LPR4;    // lanes per row (4 columns each), rows per sweep
+    const int cl = (tid % LPR4) * 4;                   // first of the lane's 4 columns inside the half
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = m0 + wm * WM + i * 32 + l32;
-      if (m >= g.M) continue;
+    for (int h = 0; h < 2; ++h) {
+      __syncthreads();
+      if (wn / WPH == h) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+        for (int i = 0; i < TM; ++i) {
+          const int ml = wm * WM + i * 32 + l32;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn * WN + j * 32 + q * 8 + lg * 4;
-          if (n >= g.N) continue;     // N is a multiple of 4: a run is in or out as a whole
-          float v0 = acc[i][j][4 * q], v1 = acc[i][j][4 * q + 1], v2 = acc[i][j][4 * q + 2], v3 = acc[i][j][4 * q + 3];
-          if (bias) {
-            const uint2 bb = *(const uint2*)(bias + n);
-            v0 += bf16_bits_to_float(bb.x & 0xffff); v1 += bf16_bits_to_float(bb.x >> 16);
-            v2 += bf16_bits_to_float(bb.y & 0xffff); v3 += bf16_bits_to_float(bb.y >> 16);
-          }
-          if constexpr (EPI == EPI_QKV) {
-            if (g.rot) {
-              const int pr = (n % g.head_dim) >> 1;   // even: two pairs = one 16-byte entry
-              const float4 cs = *(const float4*)(g.rot + (size_t)m * g.rot_pairs + pr);
-              const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
-              const float r2 = v2 * cs.z - v3 * cs.w, r3 = v2 * cs.w + v3 * cs.z;
-              v0 = r0; v1 = r1; v2 = r2; v3 = r3;
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int nl = (wn % WPH) * WN + j * 32 + q * 8 + lg * 4;
+              *(float4*)(lds + ml * ROWE + nl * 4) =
+                  make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
             }
-          }
-          if constexpr (EPI == EPI_GELU) {
-            if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
-            else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
-          }
-          if constexpr (EPI == EPI_RESIDUAL) {
-            float4* xp = (float4*)(g.resid + (size_t)m * g.ldr + n);
-            float4 x = *xp;
-            x.x += v0; x.y += v1; x.z += v2; x.w += v3;
-            *xp = x;
-          } else if constexpr (OUT == OUT_F32) {
-            *(float4*)((float*)g.out + (size_t)m * g.ldo + n) = make_float4(v0, v1, v2, v3);
-          } else {
-            *(uint2*)((uint16_t*)g.out + (size_t)m * g.ldo + n) = pack_bf16x4(v0, v1, v2, v3);
+        }
+      }
+      __syncthreads();
+      const int n = n0 + h * HALF + cl;
+      if (n >= g.N) continue;                          // N is a multiple of 4: all or nothing
+      float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+      if (bias) {
+        const uint2 bb = *(const uint2*)(bias + n);
+        b0 = bf16_bits_to_float(bb.x & 0xffff); b1 = bf16_bits_to_float(bb.x >> 16);
+        b2 = bf16_bits_to_float(bb.y & 0xffff); b3 = bf16_bits_to_float(bb.y >> 16);
+      }
+      int pr = 0;
+      if constexpr (EPI == EPI_QKV) pr = (n % g.head_dim) >> 1;   // even: two pairs = one 16-byte entry
+      for (int r = tid / LPR4; r < BM; r += RPS) {
+        const int m = m0 + r;
+        if (m >= g.M) break;
+        const float4 e = *(const float4*)(lds + r * ROWE + cl * 4);
+        float v0 = e.x + b0, v1 = e.y + b1, v2 = e.z + b2, v3 = e.w + b3;
+        if constexpr (EPI == EPI_QKV) {
+          if (g.rot) {
+            const float4 cs = *(const float4*)(g.rot + (size_t)m * g.rot_pairs + pr);
+            const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
+            const float r2 = v2 * cs.z - v3 * cs.w, r3 = v2 * cs.w + v3 * cs.z;
+            v0 = r0; v1 = r1; v2 = r2; v3 = r3;
           }
         }
+        if constexpr (EPI == EPI_GELU) {
+          if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
+          else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
+        }
+        if constexpr (EPI == EPI_RESIDUAL) {
+          float4* xp = (float4*)(g.resid + (size_t)m * g.ldr + n);
+          float4 x = *xp;
+          x.x += v0; x.y += v1; x.z += v2; x.w += v3;
+          *xp = x;
+        } else if constexpr (OUT == OUT_F32) {
+          *(float4*)((float*)g.out + (size_t)m * g.ldo + n) = make_float4(v0, v1, v2, v3);
+        } else {
+          *(uint2*)((uint16_t*)g.out + (size_t)m * g.ldo + n) = pack_bf16x4(v0, v1, v2, v3);
+        }
+      }
     }
   }
 }
@@ -272,38 +411,62 @@ __device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
   return xcd * q + min(xcd, r) + idx;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int OUT, bool GATHER>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void gemm_bf16_kernel(GemmArgs g) {
-  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  __bf16* lds = (__bf16*)lds_raw;
-  const int tiles_n = (g.N + BN - 1) / BN;
+template <class T, int EPI, int OUT, bool GATHER>
+__global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(1024))) char lds[T::LDS_BYTES];
+  const int tiles_n = (g.N + T::BN - 1) / T::BN;
   const int tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  const int m0 = (tile / tiles_n) * T::BM, n0 = (tile % tiles_n) * T::BN;
   if constexpr (EPI == EPI_QKV) {
     if (n0 >= g.qk_cols) {
-      gemm_tile<BM, BN, WAVES_M, WAVES_N, EPI, OUT, true, false>(g, m0, n0, lds);
+      gemm_tile<T, EPI, OUT, true, false>(g, m0, n0, lds);
       return;
     }
   }
-  gemm_tile<BM, BN, WAVES_M, WAVES_N, EPI, OUT, false, GATHER>(g, m0, n0, lds);
+  gemm_tile<T, EPI, OUT, false, GATHER>(g, m0, n0, lds);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int OUT, bool GATHER>
+template <class T, int EPI, int OUT, bool GATHER>
 static void launch_cfg(const GemmArgs& g, hipStream_t s) {
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  const size_t lds = (size_t)(BM + BN) * LDK * sizeof(__bf16);
-  auto kern = gemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N, EPI, OUT, GATHER>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_set = true;
-  }
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * WAVES_M * WAVES_N), lds, s, g);
+  const int tiles = ((g.M + T::BM - 1) / T::BM) * ((g.N + T::BN - 1) / T::BN);
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, GATHER>), dim3(tiles), dim3(T::NT), 0, s, g);
 }
 
+//            BM   BN  BK  WM WN MINBLK
+using T0 = Tile<256, 256, 64, 2, 4, 1>;   // 8 waves, 128x64 wave tiles, 128 KB LDS
+using T1 = Tile<256, 256, 64, 2, 2, 1>;   // 4 waves, 128x128 wave tiles
+using T2 = Tile<256, 128, 64, 2, 2, 1>;   // 96 KB LDS
+using T3 = Tile<128, 256, 64, 2, 2, 1>;
+using T4 = Tile<128, 128, 64, 2, 2, 2>;   // 64 KB LDS, two blocks per CU
+using T5 = Tile<256, 128, 32, 2, 2, 2>;   // 48 KB LDS, two blocks per CU
+
+static int forced_tile() {
+  static int t = [] {
+    const char* e = getenv("EPD_GEMM_TILE");
+    return e ? atoi(e) : -1;
+  }();
+  return t;
+}
+
+// Tile choice: the 256 x 256 tile halves the operand traffic per flop and wins once there are
+// several rounds of tiles per compute unit; small grids quantise better with 128 x 128 tiles,
+// two blocks per compute unit.
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
-  launch_cfg<256, 128, 2, 2, EPI, OUT, GATHER>(g, s);
+  int t = (g.tile_cfg & 255) > 0 ? (g.tile_cfg & 255) - 1 : forced_tile();
+  if (t < 0) {
+    const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+    t = big_tiles >= 1024 ? 0 : 4;
+  }
+  if (EPI == EPI_QKV && (t == 0 || t == 1 || t == 3) && g.qk_cols % 256 != 0) t = 2;
+  switch (t) {
+    case 0: launch_cfg<T0, EPI, OUT, GATHER>(g, s); break;
+    case 1: launch_cfg<T1, EPI, OUT, GATHER>(g, s); break;
+    case 2: launch_cfg<T2, EPI, OUT, GATHER>(g, s); break;
+    case 3: launch_cfg<T3, EPI, OUT, GATHER>(g, s); break;
+    case 5: launch_cfg<T5, EPI, OUT, GATHER>(g, s); break;
+    default: launch_cfg<T4, EPI, OUT, GATHER>(g, s); break;
+  }
 }
 
 constexpr int kQkvBN = 128;
