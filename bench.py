@@ -63,7 +63,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C2", help="C2 (headline) | C3 | C4 | C5 (other single-GPU shapes)")
     ap.add_argument("--layers", type=int, default=None, help="override depth (non-headline experiments only)")
-    ap.add_argument("--cpu-items", type=int, default=1, help="images of the batch the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-items", type=int, default=8, help="images of the batch the CPU oracle is timed on (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "

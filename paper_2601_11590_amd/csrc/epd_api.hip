@@ -151,6 +151,10 @@ epd_status validate_cfg(const epd_encode_cfg* c, bool need_buffers, std::string&
       err = "bf16: head_dim, hidden, mlp_dim, patch length and out_dim must be multiples of 8";
       return EPD_ERR_UNSUPPORTED;
     }
+    if (!c->final_norm) {
+      err = "bf16: the merger reads the normalised bf16 activations, final_norm must be 1";
+      return EPD_ERR_UNSUPPORTED;
+    }
   } else if (c->hidden % 4) {
     err = "fp32: hidden must be a multiple of 4"; return EPD_ERR_UNSUPPORTED;
   }
@@ -496,16 +500,10 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
       gemm(EPD_STEP_FC2, g);
     }
   }
-  const void* Z = nullptr;
+  const void* Z = X;   // fp32 path without a final norm reads the residual stream directly
   if (c.final_norm) {
     norm(h->at<void>(L.final_g), h->at<void>(L.final_b), Xn);
     Z = Xn;
-  } else if (bf) {
-    // the merger reads bf16 rows: without a final norm, cast the residual stream with an
-    // identity-free path is not available -> unsupported combination is rejected at create
-    Z = Xn;
-  } else {
-    Z = X;
   }
   {  // merger: gather merge x merge neighbours, project
     GemmArgs g{};

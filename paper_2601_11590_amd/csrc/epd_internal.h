@@ -24,7 +24,8 @@ struct GemmArgs {
   int lda;
   const int32_t* gather;  // optional [M, gather_n]: row m of A is the concatenation of rows
   int gather_n;           //   gather[m][0..gather_n) of A, each K/gather_n wide
-  const void* W;        // [N, K] row-major
+  const void* W;        // [N, K] row-major, leading dimension ldw (elements; 0 = K)
+  int ldw;
   const void* bias;     // [N] or nullptr
   int M, N, K;
   int epilogue;         // Epilogue

@@ -1,0 +1,148 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, the ctypes mirror of the structs matches the C layout, and every configuration
+error is reported on the host before any HIP call (no GPU needed, nothing is launched)."""
+
+import ctypes as C
+import os
+import re
+import subprocess
+import sys
+
+import pytest
+
+from paper_2601_11590_amd import binding as B, workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "epd_encode.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(epd_encode\w*)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS), (names, B.EXPORTS)
+    for n in names:
+        assert getattr(B.lib, n) is not None
+
+
+def test_header_compiles_as_plain_c_and_layout_matches_ctypes(tmp_path):
+    src = tmp_path / "probe.c"
+    fields = [f for f, _ in B.epd_encode_cfg._fields_]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "epd_encode.h"', "int main(void) {",
+             'printf("%zu %zu %zu\\n", sizeof(epd_encode_cfg), sizeof(epd_weights), sizeof(epd_layer_weights));']
+    for f in fields:
+        lines.append('printf("%s %%zu\\n", offsetof(epd_encode_cfg, %s));' % (f, f))
+    lines += ["return 0; }"]
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "probe"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, stdout=subprocess.PIPE, text=True).stdout.split("\n")
+    sizes = [int(v) for v in out[0].split()]
+    assert sizes == [C.sizeof(B.epd_encode_cfg), C.sizeof(B.epd_weights), C.sizeof(B.epd_layer_weights)]
+    for line in out[1:]:
+        if line.strip():
+            name, off = line.split()
+            assert getattr(B.epd_encode_cfg, name).offset == int(off), name
+
+
+def test_status_and_enum_values_match_header():
+    text = open(HEADER).read()
+    for name in ["EPD_OK", "EPD_ERR_INVALID_ARG", "EPD_ERR_UNSUPPORTED", "EPD_ERR_SHAPE", "EPD_ERR_WORKSPACE",
+                 "EPD_ERR_HIP", "EPD_F32", "EPD_BF16", "EPD_LAYERNORM", "EPD_RMSNORM", "EPD_GELU_ERF", "EPD_GELU_TANH",
+                 "EPD_ROPE_NONE", "EPD_ROPE_2D", "EPD_ROPE_3D", "EPD_STEP_PLAN", "EPD_STEP_MERGE", "EPD_STEP_COUNT"]:
+        m = re.search(r"\b%s\s*=\s*(-?\d+)" % name, text)
+        assert m, name
+        assert int(m.group(1)) == getattr(B, name), name
+
+
+def test_workspace_bytes_is_pure_host_arithmetic():
+    for key, cfg in W.CONFIGS.items():
+        grids = W.grids_for(cfg)
+        c = B.make_cfg(cfg, W.num_tokens(grids), len(grids), len(grids))
+        need = B.epd_encode_workspace_bytes(c)
+        params = cfg.patch_dim * cfg.hidden + cfg.num_layers * (4 * cfg.hidden ** 2 + 2 * cfg.hidden * cfg.mlp_dim) \
+            + 4 * cfg.hidden * cfg.out_dim
+        es = 4 if cfg.dtype == "f32" else 2
+        assert need > params * es, key                      # at least the weight copy
+        assert need < params * es + W.num_tokens(grids) * (cfg.hidden * 24 + cfg.mlp_dim * 4) + (64 << 20), key
+    assert B.epd_encode_workspace_bytes(B.make_cfg(W.C2, 6272, 8, 8)) % 256 == 0
+
+
+def _create_error(cfg_obj, mutate=None, max_tokens=64, with_buffers=True):
+    c = B.make_cfg(cfg_obj, max_tokens, 4, 4)
+    w = B.epd_weights()
+    lw = (B.epd_layer_weights * max(1, cfg_obj.num_layers))()
+    if with_buffers:
+        for f, _ in B.epd_layer_weights._fields_:
+            for l in lw:
+                setattr(l, f, 0x1000)
+        for f in ("patch_w", "patch_b", "final_norm_g", "final_norm_b", "merge_w", "merge_b"):
+            setattr(w, f, 0x1000)
+        w.layers = C.cast(lw, C.POINTER(B.epd_layer_weights))
+        c.weights = C.pointer(w)
+        c.workspace = 0x100000
+        c.workspace_bytes = 1 << 40
+    if mutate:
+        mutate(c)
+    h = C.c_void_p()
+    st = B.lib.epd_encode_create(C.byref(c), C.byref(h))
+    assert not h.value
+    return st, B.epd_encode_last_error(None)
+
+
+TINY = W.EncoderConfig(name="t", dtype="bf16", num_layers=1, hidden=64, num_heads=1, head_dim=64, mlp_dim=128,
+                       patch=4, temporal_patch=1, norm="rmsnorm", rope="2d", rope_pairs=(0, 16, 16), out_dim=64)
+
+
+@pytest.mark.parametrize("change,status,needle", [
+    (dict(head_dim=60, num_heads=1), B.EPD_ERR_UNSUPPORTED, "hidden"),
+    (dict(rope_pairs=(0, 16, 15)), B.EPD_ERR_UNSUPPORTED, "rope_pairs"),
+    (dict(hidden=36, num_heads=1, head_dim=36, rope_pairs=(0, 9, 9)), B.EPD_ERR_UNSUPPORTED, "multiples of 8"),
+    (dict(hidden=40, num_heads=1, head_dim=40, rope_pairs=(0, 10, 10)), B.EPD_ERR_UNSUPPORTED, "attention kernel"),
+    (dict(mlp_dim=100), B.EPD_ERR_UNSUPPORTED, "multiples of 8"),
+    (dict(num_layers=-1), B.EPD_ERR_INVALID_ARG, "non-positive"),
+    (dict(merge=0), B.EPD_ERR_INVALID_ARG, "non-positive"),
+])
+def test_create_rejects_bad_shapes_on_the_host(change, status, needle):
+    st, msg = _create_error(TINY.replace(**change))
+    assert st == status, msg
+    assert needle in msg, msg
+
+
+def test_create_rejects_bad_pointers_enums_and_workspace():
+    st, msg = _create_error(TINY, lambda c: setattr(c, "struct_size", 12))
+    assert st == B.EPD_ERR_INVALID_ARG and "struct_size" in msg
+    st, msg = _create_error(TINY, lambda c: setattr(c, "dtype", 7))
+    assert st == B.EPD_ERR_INVALID_ARG and "dtype" in msg
+    st, msg = _create_error(TINY, lambda c: setattr(c, "norm", 5))
+    assert st == B.EPD_ERR_INVALID_ARG and "norm" in msg
+    st, msg = _create_error(TINY, lambda c: setattr(c, "rope", 1))
+    assert st == B.EPD_ERR_INVALID_ARG and "rope" in msg
+    st, msg = _create_error(TINY, with_buffers=False)
+    assert st == B.EPD_ERR_INVALID_ARG and "weights" in msg
+    st, msg = _create_error(TINY, lambda c: setattr(c, "workspace", 0x100010))
+    assert st == B.EPD_ERR_WORKSPACE and "aligned" in msg
+    st, msg = _create_error(TINY, lambda c: setattr(c, "workspace_bytes", 1024))
+    assert st == B.EPD_ERR_WORKSPACE and "workspace_bytes" in msg
+    assert B.lib.epd_encode_create(None, None) == B.EPD_ERR_INVALID_ARG
+    # NULL handles are rejected by every entry point
+    assert B.lib.epd_encode(None, None, None, 0, None, 0, None, None) == B.EPD_ERR_INVALID_ARG
+    assert B.lib.epd_encode_destroy(None) == B.EPD_ERR_INVALID_ARG
+    assert B.lib.epd_encode_set_timing(None, 0) == B.EPD_ERR_INVALID_ARG
+    assert B.epd_encode_workspace_bytes(B.make_cfg(TINY.replace(head_dim=60), 64, 1, 1)) == 0
+
+
+def test_product_path_never_touches_the_oracle():
+    """The package must not import, read or execute anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_2601_11590_amd")
+    for base, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(base, f)).read()
+                assert "oracle" not in text.replace("CPU oracle", "").replace("the oracle's callers", ""), f
+    code = "import sys; import paper_2601_11590_amd.binding; assert not any(m.startswith('oracle') for m in sys.modules)"
+    subprocess.run([sys.executable, "-c", code], check=True, cwd=ROOT)

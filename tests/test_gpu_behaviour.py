@@ -1,0 +1,192 @@
+"""GPU behaviour of the C-ABI library beyond plain parity: determinism, segment isolation,
+batch invariance, error handling, handle reuse, and the shapes of the larger configurations
+(at reduced depth or sampled against the oracle, which is too slow for them in full)."""
+
+import numpy as np
+import pytest
+
+from oracle import vit_encode as O
+from paper_2601_11590_amd import workloads as W
+from parity_util import check, error_metrics, log
+
+pytestmark = pytest.mark.gpu
+
+
+def small(dtype, **kw):
+    base = dict(name="beh-" + dtype, dtype=dtype, num_layers=2, hidden=256, num_heads=4, head_dim=64,
+                mlp_dim=512, patch=4, temporal_patch=1, norm="rmsnorm", rope="2d", rope_pairs=(0, 16, 16),
+                out_dim=192, seed=5)
+    base.update(kw)
+    return W.EncoderConfig(**base)
+
+
+def make_encoder(cfg, max_tokens, segs=16, items=16):
+    from paper_2601_11590_amd import binding as B
+    gw, layers = W.all_weights(cfg)
+    return B.EpdEncoder(cfg, gw, layers, max_tokens=max_tokens, max_segments=segs, max_items=items), gw, layers
+
+
+def run(enc, cfg, patches, cu, grid, hidden=False):
+    import torch
+    from paper_2601_11590_amd import binding as B
+    y = enc.encode(B.to_device_patches(patches, cfg.dtype), cu, grid)
+    torch.cuda.synchronize()
+    out = y.float().cpu().numpy()
+    if hidden:
+        return out, enc.hidden().cpu().numpy()
+    return out
+
+
+GRIDS = [(1, 6, 10), (1, 2, 2), (1, 14, 18), (2, 4, 4)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_deterministic_isolated_and_batch_invariant(dtype):
+    cfg = small(dtype)
+    patches = W.packed_patches(cfg, GRIDS)
+    cu, grid = W.metadata(GRIDS)
+    enc, gw, layers = make_encoder(cfg, 1024)
+    try:
+        y0 = run(enc, cfg, patches, cu, grid)
+        y1 = run(enc, cfg, patches, cu, grid)
+        assert np.array_equal(y0, y1), "two calls on the same input must be bit-identical"
+        # perturb item 2 only (tokens 64..315): every other item's rows must not change at all
+        p2 = patches.copy()
+        p2[64:316] = W.round_to_dtype(p2[64:316] * 0.5 + 0.25, cfg.dtype)
+        y2 = run(enc, cfg, p2, cu, grid)
+        rows = np.cumsum([0] + [W.num_merged_tokens([g]) for g in GRIDS])
+        for i in (0, 1, 3):
+            assert np.array_equal(y0[rows[i]:rows[i + 1]], y2[rows[i]:rows[i + 1]]), "item %d changed" % i
+        assert np.abs(y0[rows[2]:rows[3]] - y2[rows[2]:rows[3]]).max() > 1e-3
+        # every item alone (same handle, smaller call) equals its rows in the batch
+        tok = 0
+        for i, g in enumerate(GRIDS):
+            n = W.num_tokens([g])
+            cu1, g1 = W.metadata([g])
+            yi = run(enc, cfg, patches[tok:tok + n], cu1, g1)
+            mabs, cos, rel = error_metrics(yi, y0[rows[i]:rows[i + 1]])
+            log("  item %d alone vs in batch: max_abs %.3e (bit-identical: %s)" % (i, mabs, mabs == 0.0))
+            assert mabs <= (1e-5 if dtype == "f32" else 2e-2 * np.abs(yi).max())
+            tok += n
+    finally:
+        enc.close()
+
+
+def test_bad_metadata_is_rejected_and_handle_survives():
+    from paper_2601_11590_amd import binding as B
+    cfg = small("bf16")
+    patches = W.packed_patches(cfg, GRIDS)
+    cu, grid = W.metadata(GRIDS)
+    enc, gw, layers = make_encoder(cfg, 512, segs=4, items=4)
+    try:
+        good = run(enc, cfg, patches, cu, grid)
+        bad_cases = [
+            (np.array([0, 60, 60, 316, 348], np.int32), grid, "increasing"),         # empty segment
+            (np.array([0, 60, 64, 316, 340], np.int32), grid, "cu_seqlens"),          # wrong total
+            (np.array([1, 60, 64, 316, 348], np.int32), grid, "cu_seqlens"),          # does not start at 0
+            (cu, np.array([[1, 6, 10], [1, 2, 2], [1, 14, 18], [2, 4, 5]], np.int32), "divisible"),
+            (cu, np.array([[1, 6, 10], [1, 2, 2], [1, 14, 18], [2, 4, 4], [1, 2, 2]], np.int32), "num_items"),
+            (np.array([0, 348, 700], np.int32), np.array([[1, 6, 10], [1, 2, 2], [1, 14, 18], [2, 4, 4], ], np.int32), "cu_seqlens"),
+        ]
+        for cu_b, grid_b, needle in bad_cases:
+            with pytest.raises(B.EpdError) as ei:
+                run(enc, cfg, patches, cu_b, grid_b)
+            assert ei.value.status == B.EPD_ERR_SHAPE, str(ei.value)
+            assert needle in str(ei.value), str(ei.value)
+        # more tokens than the handle was sized for
+        big = [(1, 20, 30)]
+        with pytest.raises(B.EpdError) as ei:
+            run(enc, cfg, W.packed_patches(cfg, big), *W.metadata(big))
+        assert ei.value.status == B.EPD_ERR_SHAPE and "max_tokens" in str(ei.value)
+        again = run(enc, cfg, patches, cu, grid)
+        assert np.array_equal(good, again)
+    finally:
+        enc.close()
+
+
+def test_smallest_inputs_and_single_token_segments():
+    # one 2x2 item (4 tokens -> 1 visual token) and per-token segments (attention = identity on V)
+    for dtype in ("f32", "bf16"):
+        cfg = small(dtype)
+        grids = [(1, 2, 2)]
+        gw, layers = W.all_weights(cfg)
+        patches = W.packed_patches(cfg, grids)
+        for cu in (np.array([0, 4], np.int32), np.array([0, 1, 2, 3, 4], np.int32)):
+            grid = np.array(grids, np.int32)
+            ref = O.encode(cfg, gw, layers, patches, cu, grid)
+            enc, _, _ = make_encoder(cfg, 4, segs=4, items=1)
+            try:
+                got = run(enc, cfg, patches, cu, grid)
+            finally:
+                enc.close()
+            assert got.shape == (1, cfg.out_dim)
+            check(cfg, got, ref, "segments=%d" % (len(cu) - 1))
+
+
+def test_permutation_equivariance_without_rotary_on_gpu():
+    cfg = small("bf16", rope="none", rope_pairs=(0, 0, 0))
+    grids = [(1, 8, 8), (1, 4, 4)]
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids)
+    enc, gw, layers = make_encoder(cfg, 128)
+    try:
+        _, h0 = run(enc, cfg, patches, cu, grid, hidden=True)
+        perm = np.arange(80)
+        perm[:64] = np.random.default_rng(1).permutation(64)
+        _, h1 = run(enc, cfg, patches[perm], cu, grid, hidden=True)
+    finally:
+        enc.close()
+    mabs, cos, rel = error_metrics(h1, h0[perm])
+    log("  permuted hidden vs permutation of hidden: max_abs %.3e min_cos %.6f" % (mabs, cos))
+    assert cos >= 0.9999 and rel <= 5e-3
+
+
+def shaped_case(cfg, grids, what):
+    log("case %s: %s" % (cfg.name, what))
+    gw, layers = W.all_weights(cfg)
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids)
+    ref = O.encode(cfg, gw, layers, patches, cu, grid)
+    from parity_util import run_gpu
+    got = run_gpu(cfg, gw, layers, patches, cu, grid)
+    return check(cfg, got, ref, what)
+
+
+def test_c3_width_varlen_one_layer():
+    # first six images of the canonical varlen batch: 384 ... 5904 tokens per segment
+    shaped_case(W.C3.replace(num_layers=1), W.grids_for(W.C3)[:6], "6 varlen images, L=1")
+
+
+def test_c4_shape_head_dim_72_one_layer():
+    # hidden 1152 = 16 x 72, MLP 4304 (K tail of 16), one 1344 x 1344 image = 7056 tokens
+    shaped_case(W.C4.replace(num_layers=1), [(1, 84, 84)], "d=72, 7056-token single sequence, L=1")
+
+
+def test_c5_shape_video_3d_rotary_one_layer():
+    # hidden 3200 = 25 x 128, MLP 12800, patch 14 x temporal 2 (K = 1176, tail of 24), 3-D rotary
+    shaped_case(W.C5.replace(num_layers=1), [(4, 16, 16), (2, 16, 32)], "video clips, L=1")
+
+
+def test_c2_full_depth_batch_sampled_against_oracle():
+    """The benchmark configuration as bench.py launches it (8 images, 24 layers); the oracle
+    recomputes the first and the last image alone, which block-diagonal attention makes equal
+    to their rows in the batch."""
+    from paper_2601_11590_amd import binding as B
+    import torch
+    cfg = W.C2
+    grids = W.grids_for(cfg)
+    gw, layers = W.all_weights(cfg)
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids)
+    enc = B.EpdEncoder(cfg, gw, layers, max_tokens=patches.shape[0], max_segments=8, max_items=8)
+    try:
+        got = enc.encode(B.to_device_patches(patches, cfg.dtype), cu, grid)
+        torch.cuda.synchronize()
+        got = got.float().cpu().numpy()
+    finally:
+        enc.close()
+    assert got.shape == (1568, 4096) and np.isfinite(got).all()
+    for item in (0, 7):
+        cu1, g1 = W.metadata([grids[item]])
+        ref = O.encode(cfg, gw, layers, patches[784 * item:784 * (item + 1)], cu1, g1)
+        check(cfg, got[196 * item:196 * (item + 1)], ref, "image %d of 8, 24 layers" % item)
