@@ -64,7 +64,18 @@ def main():
     ap.add_argument("--config", default="C2", help="C2 (headline) | C3 | C4 | C5 (other single-GPU shapes)")
     ap.add_argument("--layers", type=int, default=None, help="override depth (non-headline experiments only)")
     ap.add_argument("--cpu-items", type=int, default=8, help="images of the batch the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[bench] copied 5 x 1 GiB (reads 1 GiB and writes 1 GiB per launch)")
+        return
     if args.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
             "--gpus %d is not supported. Items would shard across GPUs by image with replicated "

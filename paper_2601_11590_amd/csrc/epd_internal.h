@@ -45,6 +45,7 @@ struct GemmArgs {
   const int32_t* vcol;  // [M] column of token m in vt
   const void* zeros;    // bf16 path: >= 16 readable zero bytes (source of out-of-range tile chunks)
   int tile_cfg;         // bf16 path: 0 = automatic choice, k > 0 = tile variant k - 1 (tuning)
+  int group_m;          // bf16 path: row tiles per rasterisation group (set by the launcher)
 };
 
 // ---------------------------------------------------------------- attention description

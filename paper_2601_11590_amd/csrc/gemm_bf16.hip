@@ -24,6 +24,7 @@
 // attention kernel's second GEMM.
 #include "epd_internal.h"
 
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 
@@ -203,6 +204,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   // that load inserted in front of it, which would serialise the two-stage ring).
   // Row of lane = wave row + i*32 + l32; multiples of 32 keep swz(row) = swz(l32).
   constexpr int KS = BK / 16, NF = TM + TN;
+  constexpr bool LATE_REFILL = TM * TN <= 4;
   const uint32_t lds0 = (uint32_t)(size_t)EPD_LPTR(lds);
   uint32_t a_rd[2][KS], w_rd[2][KS];
 #pragma unroll
@@ -270,12 +272,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
           wait_vmcnt<0>();
           wait_frags(I1{}, I0{});
           if (!(g.tile_cfg & 512)) __builtin_amdgcn_s_barrier();
-          if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(lds + s * T::STAGE_BYTES, kt + 2);
+          if constexpr (!LATE_REFILL) {
+            if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(lds + s * T::STAGE_BYTES, kt + 2);
+          }
           read_frags(I0{}, SN{}, I0{});
         } else {
           wait_frags(I1{}, I0{});
         }
         mfmas(I1{});
+        if constexpr (LATE_REFILL) {
+          // small wave tiles: the refill of stage s is issued behind the queued MFMAs, so the
+          // address arithmetic and load instructions run in their shadow (pinning this order
+          // costs registers, which the large wave tiles do not have)
+          __builtin_amdgcn_sched_barrier(0);
+          if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(lds + s * T::STAGE_BYTES, kt + 2);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
   };
@@ -408,21 +420,33 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   }
 }
 
-// Consecutive hardware block ids go to different XCDs (8 per chip, each with its own L2).
-// Remap so that every XCD walks a contiguous range of tiles, N fastest: neighbouring blocks
-// of one XCD then share the same A row panel and sweep W.
+// Consecutive hardware block ids go to different XCDs (8 per chip, each with its own 4 MB
+// L2).  Remap so that every XCD walks a contiguous range of tile numbers, and number the tiles
+// in groups of `group_m` row tiles swept column by column: the tiles an XCD runs at the same
+// time then form a compact rectangle whose A panels stay in its L2 while W panels stream
+// through once, instead of every XCD re-reading all of W for every row of tiles.
 __device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
   const int q = nblocks >> 3, r = nblocks & 7;
   const int xcd = bid & 7, idx = bid >> 3;
   return xcd * q + min(xcd, r) + idx;
 }
 
+__device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int group_m, int& tm, int& tn) {
+  const int per_group = group_m * tiles_n;
+  const int grp = t / per_group, local = t - grp * per_group;
+  const int first = grp * group_m;
+  const int rows = min(group_m, tiles_m - first);
+  tn = local / rows;
+  tm = first + (local - tn * rows);
+}
+
 template <class T, int EPI, int OUT, bool GATHER>
 __global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(1024))) char lds[T::LDS_BYTES];
-  const int tiles_n = (g.N + T::BN - 1) / T::BN;
-  const int tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int m0 = (tile / tiles_n) * T::BM, n0 = (tile % tiles_n) * T::BN;
+  const int tiles_n = (g.N + T::BN - 1) / T::BN, tiles_m = (g.M + T::BM - 1) / T::BM;
+  int tm, tn;
+  tile_coords(xcd_remap(blockIdx.x, gridDim.x), tiles_m, tiles_n, g.group_m, tm, tn);
+  const int m0 = tm * T::BM, n0 = tn * T::BN;
   if constexpr (EPI == EPI_QKV) {
     if (n0 >= g.qk_cols) {
       gemm_tile<T, EPI, OUT, true, false>(g, m0, n0, lds);
@@ -434,8 +458,15 @@ __global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g)
 
 template <class T, int EPI, int OUT, bool GATHER>
 static void launch_cfg(const GemmArgs& g, hipStream_t s) {
-  const int tiles = ((g.M + T::BM - 1) / T::BM) * ((g.N + T::BN - 1) / T::BN);
-  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, GATHER>), dim3(tiles), dim3(T::NT), 0, s, g);
+  const int tiles_m = (g.M + T::BM - 1) / T::BM, tiles_n = (g.N + T::BN - 1) / T::BN;
+  GemmArgs a = g;
+  if (a.group_m <= 0) {
+    // keep the A panels of one group (group_m x BM rows x K) within about 2 MB of the 4 MB L2
+    const long panel = (long)T::BM * g.K * 2;
+    a.group_m = (int)std::max(1L, std::min((long)tiles_m, (2L << 20) / std::max(panel, 1L)));
+  }
+  a.group_m = std::min(a.group_m, tiles_m);
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, GATHER>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
 }
 
 //            BM   BN  BK  WM WN MINBLK
