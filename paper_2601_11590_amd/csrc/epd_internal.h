@@ -46,6 +46,7 @@ struct GemmArgs {
   const void* zeros;    // bf16 path: >= 16 readable zero bytes (source of out-of-range tile chunks)
   int tile_cfg;         // bf16 path: 0 = automatic choice, k > 0 = tile variant k - 1 (tuning)
   int group_m;          // bf16 path: row tiles per rasterisation group (set by the launcher)
+  unsigned long long* trace;  // tuning builds only (EPD_GEMM_TRACE): per-wave stall cycle counters
 };
 
 // ---------------------------------------------------------------- attention description

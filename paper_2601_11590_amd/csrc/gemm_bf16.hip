@@ -249,6 +249,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   // barrier (everybody's loads landed, everybody finished reading stage s), refill stage s
   // with K step kt+2, start reading stage s^1 -- and only then issue the MFMAs of the last
   // slice, which cover the barrier and the LDS latency.  Every load has one full K step to land.
+#ifdef EPD_GEMM_TRACE
+  unsigned long long tr_vm = 0, tr_bar = 0;
+  const unsigned long long tr_start = __builtin_readcyclecounter();
+#endif
   issue_step(lds, 0);
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
@@ -269,9 +273,19 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       } else {
         // last slice (fragment buffer 1): stage hand-over first
         if (kt + 1 < nk) {
+#ifdef EPD_GEMM_TRACE
+          wait_frags(I1{}, I0{});
+          const unsigned long long c0 = __builtin_readcyclecounter();
+          wait_vmcnt<0>();
+          const unsigned long long c1 = __builtin_readcyclecounter();
+          if (!(g.tile_cfg & 512)) __builtin_amdgcn_s_barrier();
+          const unsigned long long c2 = __builtin_readcyclecounter();
+          tr_vm += c1 - c0; tr_bar += c2 - c1;
+#else
           wait_vmcnt<0>();
           wait_frags(I1{}, I0{});
           if (!(g.tile_cfg & 512)) __builtin_amdgcn_s_barrier();
+#endif
           if constexpr (!LATE_REFILL) {
             if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(lds + s * T::STAGE_BYTES, kt + 2);
           }
@@ -296,6 +310,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     if (kt + 1 < nk) step(I1{}, kt + 1);
   }
 
+#ifdef EPD_GEMM_TRACE
+  const unsigned long long tr_loop_end = __builtin_readcyclecounter();
+#endif
   // ------------------------------------------------------------------ epilogue
   // The accumulators go through LDS (the operand stages are dead by now) so that global
   // memory sees row-contiguous accesses: straight from the MFMA layout every store
@@ -418,6 +435,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       }
     }
   }
+#ifdef EPD_GEMM_TRACE
+  if (g.trace && lane == 0) {
+    const unsigned long long tr_end = __builtin_readcyclecounter();
+    unsigned long long* t = g.trace + ((size_t)blockIdx.x * (NT / 64) + wave) * 4;
+    t[0] = tr_vm; t[1] = tr_bar; t[2] = tr_loop_end - tr_start; t[3] = tr_end - tr_loop_end;
+  }
+#endif
 }
 
 // Consecutive hardware block ids go to different XCDs (8 per chip, each with its own 4 MB
