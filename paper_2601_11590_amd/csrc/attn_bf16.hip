@@ -7,34 +7,47 @@
 // head; a wave owns NQ groups of 32 query rows):
 //   * Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then
 //     holds ONE query column (lane % 32) and 16 key rows per 32x32 tile, so the running
-//     maximum and the running sum of the softmax are per-lane scalars; one exchange with
-//     lane ^ 32 per key tile completes the maximum, the sums are merged once at the end.
+//     maximum and the running sum of the softmax are per-lane scalars; one exchange between
+//     the two lane halves (v_permlane32_swap) per key tile completes the maximum, the sums
+//     are merged once at the end.
 //   * The accumulator layout of S^T (key rows 8*(v/4) + 4*(lane/32) + v%4) is, after rounding
 //     to bf16, directly the second MFMA operand of O^T = V^T P^T, provided the first operand
 //     (V^T) enumerates the keys in the same order.  V is therefore kept transposed
 //     ([channel][token], written that way by the QKV GEMM) and a lane reads its 2 x 4 keys
 //     with two 8-byte LDS reads.  No data ever moves between lanes for P.
-//   * K tiles ([64 keys][d], 16-byte padded rows) and V^T tiles ([d][64 keys], 8-byte padded
-//     rows) are staged through LDS once per block and shared by its 4 waves; Q stays in
-//     registers as MFMA operands for the whole kernel.
-//   * exp is v_exp_f32 (base 2) with 1/sqrt(d) * log2(e) folded into one fused multiply-add.
-// Head dimensions that are not multiples of 16 / 32 are zero-padded inside LDS only.
+//   * K tiles ([64 keys][d]) and V^T tiles ([d][64 keys]) go from global memory straight into
+//     LDS (global_load_lds_dwordx4) in a two-stage ring: the tile after the current one is in
+//     flight while the current one is multiplied, one barrier per key tile.  Rows of 128 bytes
+//     are XOR-swizzled at 16-byte granularity for the 64-bank LDS; fragment reads are
+//     explicit ds_read instructions with counted waits so that they are never serialised
+//     against the loads in flight.  Q stays in registers as MFMA operands for the whole kernel.
+//   * exp is v_exp_f32 (base 2) with 1/sqrt(d) * log2(e) folded into one fused multiply-add;
+//     the softmax reference value trails the running maximum by up to 8 (log2 units), so the
+//     output accumulators are rescaled only rarely (and then for the whole wave).
+// Head dimensions that are not multiples of 16 / 32 are handled by zeroing the Q operand
+// beyond d and never storing output rows beyond d.
 #include "epd_internal.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace epd {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define EPD_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define EPD_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 constexpr int BKV = 64;
+constexpr float kLag = 8.0f;   // slack of the running softmax reference, in log2 units
 
 union Frag8 {
   bf16x8 v;
   uint4 u;
-  uint2 h[2];
+  u32x2 h[2];
   uint32_t w[4];
 };
 
@@ -44,43 +57,117 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
   return *(uint32_t*)&t;
 }
 
+template <int OFF> __device__ __forceinline__ void lds_read16(bf16x8& d, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int OFF> __device__ __forceinline__ void lds_read8(u32x2& d, uint32_t addr) {
+  asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
+}
+template <int PENDING> __device__ __forceinline__ void lds_wait() {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(PENDING) : "memory");
+}
+__device__ __forceinline__ void tie(bf16x8& f) { asm volatile("" : "+v"(f)); }
+
+// max over the two halves of the wave (lane l and lane l ^ 32)
+__device__ __forceinline__ float half_swap_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <int DH, int NQ, int MINBLK>
 __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   constexpr int KS = (DH + 15) / 16;       // k-steps of the score GEMM
-  constexpr int DHP = KS * 16;             // K row length in LDS (zero padded)
   constexpr int DB = (DH + 31) / 32;       // 32-row blocks of O^T
-  constexpr int KSTR = DHP + 8;            // K row stride (elements): 16-byte pad
-  constexpr int VSTR = BKV + 4;            // V^T row stride (elements): 8-byte pad
-  constexpr int BQ = 128 * NQ;
-
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[BKV * KSTR];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[DB * 32 * VSTR];
+  constexpr int CPRK = DH / 8;             // 16-byte chunks per K row
+  constexpr int ROWK = DH * 2;             // bytes per K row in LDS
+  constexpr int KBYTES = BKV * ROWK;
+  constexpr int VBYTES = DH * 128;         // V^T tile: DH rows of 64 keys
+  constexpr int STAGE = KBYTES + VBYTES;
+  constexpr int LK = (BKV * CPRK + 255) / 256, LV = (DH * 8 + 255) / 256;
+  // K row swizzle: power-of-two rows need one (all rows would start in the same banks);
+  // 144-byte rows (d = 72) already spread 16 consecutive rows over all 64 banks
+  constexpr bool SWZK = (CPRK & (CPRK - 1)) == 0;
+  // slack: fragment reads of padded head dims run past the tile (V^T rows up to DB*32, the
+  // K chunk beyond d); what they fetch only meets zero Q operands or unstored output rows
+  __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE + (DB * 32 - DH) * 128 + 64];
 
   const AttnWork w = a.work[blockIdx.x];
   const int head = blockIdx.y;
   const int D = a.num_heads * DH;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, lg = lane >> 5;
   const int seg_end = w.seg_start + w.seg_len;
   const uint16_t* qk = (const uint16_t*)a.qkv;
-  const uint16_t* vt = (const uint16_t*)a.vt + (size_t)head * DH * a.vt_stride + w.vcol0;
+  const char* kbase = (const char*)(qk + (size_t)w.seg_start * a.ld_qkv + D + head * DH);
+  const char* vbase = (const char*)((const uint16_t*)a.vt + (size_t)head * DH * a.vt_stride + w.vcol0);
+  const int ntiles = (w.seg_len + BKV - 1) / BKV;
 
-  // zero the LDS padding once (K columns DH..DHP, V^T rows DH..DB*32); loads never touch it
-  if constexpr (DHP > DH) {
-    for (int i = tid; i < BKV * (DHP - DH); i += 256) {
-      const int r = i / (DHP - DH), c = DH + i % (DHP - DH);
-      ((uint16_t*)Ks)[r * KSTR + c] = 0;
+  // ---- load descriptors (direct-to-LDS: lane i of an instruction fills LDS chunk base + i)
+  int k_row[LK], k_ch[LK];
+  bool k_on[LK];
+#pragma unroll
+  for (int it = 0; it < LK; ++it) {
+    const int lin = it * 256 + tid;
+    k_on[it] = lin < BKV * CPRK;
+    const int row = lin / CPRK, slot = lin - row * CPRK;
+    k_row[it] = row;
+    k_ch[it] = SWZK ? (slot ^ ((CPRK == 8 ? (row >> 1) : row) & (CPRK - 1))) : slot;
+  }
+  uint32_t v_off[LV];
+  bool v_on[LV];
+#pragma unroll
+  for (int it = 0; it < LV; ++it) {
+    const int lin = it * 256 + tid;
+    v_on[it] = lin < DH * 8;
+    const int row = lin >> 3, slot = lin & 7;
+    v_off[it] = (uint32_t)row * (uint32_t)a.vt_stride * 2u + (uint32_t)((slot ^ ((row >> 1) & 7)) * 16);
+  }
+  auto issue = [&](int st, int tile) {
+    char* sb = lds + st * STAGE;
+    const int kv0 = tile * BKV;
+#pragma unroll
+    for (int it = 0; it < LK; ++it) {
+      if (k_on[it]) {
+        const int r = min(kv0 + k_row[it], w.seg_len - 1);   // rows past the segment repeat its last key (masked later)
+        const char* p = kbase + (size_t)r * a.ld_qkv * 2 + k_ch[it] * 16;
+        __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(sb + (it * 256 + wave * 64) * 16), 16, 0, 0);
+      }
     }
+    const char* vb = vbase + (size_t)kv0 * 2;
+#pragma unroll
+    for (int it = 0; it < LV; ++it) {
+      if (v_on[it])
+        __builtin_amdgcn_global_load_lds(EPD_GPTR(vb + v_off[it]), EPD_LPTR(sb + KBYTES + (it * 256 + wave * 64) * 16), 16, 0, 0);
+    }
+  };
+
+  // ---- fragment read addresses (stage 0; stage 1 and row blocks through the offset field)
+  const uint32_t lds0 = (uint32_t)(size_t)EPD_LPTR(lds);
+  uint32_t k_rd[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const int ch = ks * 2 + lg;
+    const int slot = SWZK ? (ch ^ ((CPRK == 8 ? (l32 >> 1) : l32) & (CPRK - 1))) : ch;
+    k_rd[ks] = lds0 + l32 * ROWK + slot * 16;
   }
-  if constexpr (DB * 32 > DH) {
-    for (int i = tid; i < (DB * 32 - DH) * VSTR; i += 256) ((uint16_t*)Vs)[DH * VSTR + i] = 0;
-  }
+  uint32_t v_rd[8];   // chunk kb*4 + mm*2 + half of row l32 (row blocks of 32 keep the swizzle)
+#pragma unroll
+  for (int c = 0; c < 8; ++c) v_rd[c] = lds0 + KBYTES + l32 * 128 + ((c ^ ((l32 >> 1) & 7)) * 16) + lg * 8;
+
+  // a wave none of whose query rows exist still takes part in loads and barriers only
+  const int q_wave0 = w.q0 + wave * 32 * NQ;
+  const bool wave_active = q_wave0 < seg_end;
 
   // Q fragments (second MFMA operand of S^T = K Q^T): lane = query column, 8 consecutive d
   Frag8 qf[NQ][KS];
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
-    const int qrow = w.q0 + wave * 32 * NQ + nq * 32 + l32;
+    const int qrow = q_wave0 + nq * 32 + l32;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int d = ks * 16 + lg * 8;
@@ -102,27 +189,10 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
 
   const float c = a.scale * 1.44269504088896340736f;   // scores are handled in log2 units
 
-  for (int kv0 = 0; kv0 < w.seg_len; kv0 += BKV) {
-    const int nvalid = w.seg_len - kv0;   // >= 1
-    __syncthreads();
-    // K tile: 64 rows x DH/8 chunks of 16 bytes
-    for (int i = tid; i < BKV * (DH / 8); i += 256) {
-      const int r = i / (DH / 8), ch = i % (DH / 8);
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (r < nvalid) v = *(const uint4*)(qk + (size_t)(w.seg_start + kv0 + r) * a.ld_qkv + D + head * DH + ch * 8);
-      *(uint4*)((uint16_t*)Ks + r * KSTR + ch * 8) = v;
-    }
-    // V^T tile: DH rows x 8 chunks of 16 bytes (columns beyond the segment are zero in memory)
-    for (int i = tid; i < DH * (BKV / 8); i += 256) {
-      const int r = i >> 3, ch = i & 7;
-      const uint4 v = *(const uint4*)(vt + (size_t)r * a.vt_stride + kv0 + ch * 8);
-      uint2* dst = (uint2*)((uint16_t*)Vs + r * VSTR + ch * 8);
-      dst[0] = make_uint2(v.x, v.y);
-      dst[1] = make_uint2(v.z, v.w);
-    }
-    __syncthreads();
-
-    // ---- S^T = K Q^T
+  auto compute = [&](auto ST, int nvalid) {
+    constexpr int st = decltype(ST)::value;
+    constexpr int SO = st * STAGE;
+    // ---- S^T = K Q^T: K fragments of k-step ks+1 are requested before step ks is multiplied
     f32x16 s[2][NQ];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -130,16 +200,25 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
       for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[kb][nq][v] = 0.f;
+    bf16x8 kf[2][2];
+    lds_read16<SO>(kf[0][0], k_rd[0]);
+    lds_read16<SO + 32 * ROWK>(kf[0][1], k_rd[0]);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 kf[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) kf[kb] = *(const bf16x8*)(Ks + (kb * 32 + l32) * KSTR + ks * 16 + lg * 8);
+      const int cur = ks & 1;
+      if (ks + 1 < KS) {
+        lds_read16<SO>(kf[cur ^ 1][0], k_rd[ks + 1 < KS ? ks + 1 : 0]);
+        lds_read16<SO + 32 * ROWK>(kf[cur ^ 1][1], k_rd[ks + 1 < KS ? ks + 1 : 0]);
+        lds_wait<2>();
+      } else {
+        lds_wait<0>();
+      }
+      tie(kf[cur][0]); tie(kf[cur][1]);
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq)
-          s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb], qf[nq][ks].v, s[kb][nq], 0, 0, 0);
+          s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[cur][kb], qf[nq][ks].v, s[kb][nq], 0, 0, 0);
     }
     if (nvalid < BKV) {
 #pragma unroll
@@ -156,6 +235,8 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
 
     // ---- online softmax, per query column (= per lane pair l, l ^ 32)
     Frag8 pb[NQ][2][2];
+    float alpha[NQ];
+    bool moved = false;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
       float mx = s[0][nq][0];
@@ -163,9 +244,14 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][nq][v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mnew = fmaxf(mrun[nq], mx * c);
-      const float alpha = __builtin_amdgcn_exp2f(mrun[nq] - mnew);
+      mx = half_swap_max(mx) * c;
+      // the reference maximum only follows the true one when it falls behind by more than
+      // kLag (log2 units): in between, probabilities may reach 2^kLag instead of 1, which
+      // fp32 sums and bf16 operands hold without loss, and no rescale is needed
+      const bool lag = mx > mrun[nq] + kLag;
+      const float mnew = lag ? mx : mrun[nq];
+      alpha[nq] = __builtin_amdgcn_exp2f(mrun[nq] - mnew);
+      moved = moved || lag;
       mrun[nq] = mnew;
       float psum = 0.f;
 #pragma unroll
@@ -179,36 +265,75 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
             psum += p0 + p1;
             pb[nq][kb][mm].w[e >> 1] = pack2(p0, p1);
           }
-      lrun[nq] = lrun[nq] * alpha + psum;
+      lrun[nq] = lrun[nq] * alpha[nq] + psum;
+    }
+    // rescale the output accumulators only if some row's maximum moved (wave-uniform test)
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+      for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[db][nq][v] *= alpha;
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[db][nq][v] *= alpha[nq];
     }
 
-    // ---- O^T += V^T P^T
+    // ---- O^T += V^T P^T: fragments of one 32-channel block are requested ahead of its MFMAs
+    Frag8 vf[2][4];
+    auto read_v = [&](auto DBI, int buf) {
+      constexpr int off = SO + decltype(DBI)::value * 32 * 128;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int f = 0; f < 4; ++f) {   // f = kb*2 + mm
+        lds_read8<off>(vf[buf][f].h[0], v_rd[2 * f]);
+        lds_read8<off>(vf[buf][f].h[1], v_rd[2 * f + 1]);
+      }
+    };
+    auto pv = [&](int db, int buf) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int f = 0; f < 4; ++f) {
+        tie(vf[buf][f].v);
 #pragma unroll
-        for (int mm = 0; mm < 2; ++mm) {
-          Frag8 vf;
-          const uint16_t* src = (const uint16_t*)Vs + (db * 32 + l32) * VSTR + kb * 32 + 16 * mm + 4 * lg;
-          vf.h[0] = *(const uint2*)src;
-          vf.h[1] = *(const uint2*)(src + 8);
-#pragma unroll
-          for (int nq = 0; nq < NQ; ++nq)
-            o[db][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pb[nq][kb][mm].v, o[db][nq], 0, 0, 0);
-        }
+        for (int nq = 0; nq < NQ; ++nq)
+          o[db][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[buf][f].v, pb[nq][f >> 1][f & 1].v, o[db][nq], 0, 0, 0);
+      }
+    };
+    read_v(std::integral_constant<int, 0>{}, 0);
+    if constexpr (DB > 1) { read_v(std::integral_constant<int, 1>{}, 1); lds_wait<8>(); } else { lds_wait<0>(); }
+    pv(0, 0);
+    if constexpr (DB > 1) {
+      if constexpr (DB > 2) { read_v(std::integral_constant<int, 2>{}, 0); lds_wait<8>(); } else { lds_wait<0>(); }
+      pv(1, 1);
+    }
+    if constexpr (DB > 2) {
+      if constexpr (DB > 3) { read_v(std::integral_constant<int, 3>{}, 1); lds_wait<8>(); } else { lds_wait<0>(); }
+      pv(2, 0);
+    }
+    if constexpr (DB > 3) {
+      lds_wait<0>();
+      pv(3, 1);
+    }
+  };
+
+  // ---- key tiles: two-stage ring, the next tile is in flight while this one is multiplied
+  issue(0, 0);
+  for (int j = 0; j < ntiles; j += 2) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    if (j + 1 < ntiles) issue(1, j + 1);
+    if (wave_active) compute(std::integral_constant<int, 0>{}, w.seg_len - j * BKV);
+    if (j + 1 < ntiles) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      if (j + 2 < ntiles) issue(0, j + 2);
+      if (wave_active) compute(std::integral_constant<int, 1>{}, w.seg_len - (j + 1) * BKV);
+    }
   }
 
   // ---- normalise and store: lane owns runs of 4 consecutive channels of one query row
   uint16_t* out = (uint16_t*)a.out;
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
-    const int qrow = w.q0 + wave * 32 * NQ + nq * 32 + l32;
-    const float ltot = lrun[nq] + __shfl_xor(lrun[nq], 32);
+    const int qrow = q_wave0 + nq * 32 + l32;
+    const float ltot = half_swap_sum(lrun[nq]);
     if (qrow >= seg_end) continue;
     const float inv = 1.0f / ltot;
 #pragma unroll
@@ -225,15 +350,19 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   }
 }
 
-static int bf16_nq() {
-  static int nq = [] {
+// Query rows per work item.  Two 32-row groups per wave (256-row tiles) halve the LDS
+// fragment traffic per MFMA and win for d <= 64 on long segments; otherwise one group per
+// wave (128-row tiles) keeps two waves per SIMD resident and wastes less on segment tails.
+static int bf16_nq(int head_dim, int max_seg_len) {
+  static int forced = [] {
     const char* e = getenv("EPD_ATTN_NQ");
-    return (e && e[0] == '1') ? 1 : 2;
+    return e ? atoi(e) : 0;
   }();
-  return nq;
+  if (forced == 1 || forced == 2) return forced;
+  return (head_dim <= 64 && max_seg_len > 1024) ? 2 : 1;
 }
 
-int attn_q_tile(bool bf16, int head_dim) {
+int attn_q_tile(bool bf16, int head_dim, int max_seg_len) {
   if (!bf16) {
     switch (head_dim) {
       case 8: case 16: case 32: case 64: case 72: case 80: case 96: case 128: return 64;
@@ -241,7 +370,7 @@ int attn_q_tile(bool bf16, int head_dim) {
     }
   }
   switch (head_dim) {
-    case 32: case 64: case 72: case 80: case 96: case 128: return 128 * bf16_nq();
+    case 32: case 64: case 72: case 80: case 96: case 128: return 128 * bf16_nq(head_dim, max_seg_len);
     default: return 0;
   }
 }
@@ -249,7 +378,7 @@ int attn_q_tile(bool bf16, int head_dim) {
 bool launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.num_work <= 0) return true;
   dim3 grid(a.num_work, a.num_heads), block(256);
-  const int nq = bf16_nq();
+  const int nq = a.q_tile / 128;
 #define EPD_ATTN(DH, MB2)                                                                    \
   case DH:                                                                                   \
     if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, MB2>), grid, block, 0, s, a);   \

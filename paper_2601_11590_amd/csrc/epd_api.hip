@@ -50,7 +50,7 @@ struct Layout {
 
 constexpr size_t kAbsent = (size_t)-1;
 
-int q_tile(const epd_encode_cfg& c) { return attn_q_tile(c.dtype == EPD_BF16, c.head_dim); }
+int q_tile(const epd_encode_cfg& c, int max_seg_len) { return attn_q_tile(c.dtype == EPD_BF16, c.head_dim, max_seg_len); }
 
 Layout make_layout(const epd_encode_cfg& c) {
   Layout L;
@@ -62,7 +62,7 @@ Layout make_layout(const epd_encode_cfg& c) {
   L.pairs = c.rope == EPD_ROPE_NONE ? 0 : c.head_dim / 2;
   L.mm = c.merge * c.merge;
   L.max_tm = c.max_tokens / L.mm;
-  L.max_work = c.max_tokens / q_tile(c) + c.max_segments + 1;
+  L.max_work = c.max_tokens / q_tile(c, 1) + c.max_segments + 1;   // smallest tile the kernels use
   L.vt_stride = (int)align_up((size_t)c.max_tokens + (size_t)c.max_segments * kVtAlign, kVtAlign);
   const bool ln = c.norm == EPD_LAYERNORM, bias = c.use_bias != 0;
   size_t off = 0;
@@ -158,7 +158,7 @@ epd_status validate_cfg(const epd_encode_cfg* c, bool need_buffers, std::string&
   } else if (c->hidden % 4) {
     err = "fp32: hidden must be a multiple of 4"; return EPD_ERR_UNSUPPORTED;
   }
-  if (attn_q_tile(c->dtype == EPD_BF16, c->head_dim) <= 0) {
+  if (attn_q_tile(c->dtype == EPD_BF16, c->head_dim, 1) <= 0) {
     err = fmt("head_dim %d has no attention kernel for this dtype", c->head_dim);
     return EPD_ERR_UNSUPPORTED;
   }
@@ -397,7 +397,9 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
   }
   // attention work list: one entry per query tile, longest segments first so that the tail
   // of the launch is made of short items
-  const int bq = q_tile(c);
+  int max_len = 0;
+  for (int s = 0; s < S; ++s) max_len = std::max(max_len, cu[s + 1] - cu[s]);
+  const int bq = q_tile(c, max_len);
   std::vector<int> order(S);
   for (int s = 0; s < S; ++s) order[s] = s;
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
@@ -473,7 +475,7 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
       AttnArgs a{};
       a.qkv = QKV; a.ld_qkv = bf ? 2 * D : 3 * D; a.vt = Vt; a.vt_stride = L.vt_stride;
       a.out = O; a.ld_out = D; a.work = d_work; a.num_work = nwork;
-      a.num_heads = c.num_heads; a.head_dim = c.head_dim; a.scale = (float)(1.0 / std::sqrt((double)c.head_dim));
+      a.num_heads = c.num_heads; a.head_dim = c.head_dim; a.q_tile = bq; a.scale = (float)(1.0 / std::sqrt((double)c.head_dim));
       double flops = 0.0;
       for (int s = 0; s < S; ++s) { double n = cu[s + 1] - cu[s]; flops += 4.0 * n * n * D; }
       StepTimer tm(h, EPD_STEP_ATTN, flops, st);

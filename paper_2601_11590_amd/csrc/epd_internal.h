@@ -64,6 +64,7 @@ struct AttnArgs {
   int num_work;
   int num_heads, head_dim;
   float scale;          // 1 / sqrt(head_dim)
+  int q_tile;           // query rows per work item (attn_q_tile of this call)
 };
 
 // ---------------------------------------------------------------- plan (per-call metadata)
@@ -93,7 +94,9 @@ void launch_gemm_f32(const GemmArgs& g, hipStream_t s);
 bool launch_attn_f32(const AttnArgs& a, hipStream_t s);   // false: head_dim not covered
 void launch_gemm_bf16(const GemmArgs& g, hipStream_t s);
 bool launch_attn_bf16(const AttnArgs& a, hipStream_t s);  // false: head_dim not covered
-int attn_q_tile(bool bf16, int head_dim);                 // query rows per work item
+// query rows per work item for segments up to max_seg_len (0 = unsupported head_dim);
+// never smaller than attn_q_tile(bf16, head_dim, 1)
+int attn_q_tile(bool bf16, int head_dim, int max_seg_len);
 // dst[(sec, h, 2p+e)] = src[(sec, h, p + e*pairs)] for the Q and K sections, V copied
 void launch_permute_qkv(const void* src_w, const void* src_b, void* dst_w, void* dst_b,
                         int hidden, int num_heads, int head_dim, int elem_bytes, hipStream_t s);
