@@ -139,22 +139,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   const int ldw = g.ldw ? g.ldw : g.K;
   const char* w_base_ptr = (const char*)g.W + (size_t)n0 * ldw * 2;
   uint32_t a_off[LA], w_off[LW];
-  int a_col[LA], w_col[LW], a_row[LA];
 #pragma unroll
   for (int it = 0; it < LA; ++it) {
     const int c = it * NT + tid, row = c / CPR, col = (c % CPR) ^ T::swz(row);
-    const int r = min(row, g.M - 1 - m0);
-    a_col[it] = col * 8;
-    a_row[it] = m0 + r;
-    a_off[it] = (uint32_t)r * (uint32_t)g.lda * 2u + col * 16;
+    a_off[it] = (uint32_t)min(row, g.M - 1 - m0) * (uint32_t)g.lda * 2u + col * 16;
   }
 #pragma unroll
   for (int it = 0; it < LW; ++it) {
     const int c = it * NT + tid, row = c / CPR, col = (c % CPR) ^ T::swz(row);
-    const int r = min(row, g.N - 1 - n0);
-    w_col[it] = col * 8;
-    w_off[it] = (uint32_t)r * (uint32_t)ldw * 2u + col * 16;
+    w_off[it] = (uint32_t)min(row, g.N - 1 - n0) * (uint32_t)ldw * 2u + col * 16;
   }
+  // first k of the chunk that load instruction `it` fetches (only the ragged-K and gather paths
+  // need it, so it is recomputed there rather than kept in registers)
+  auto chunk_k = [&](int it) {
+    const int c = it * NT + tid, row = c / CPR;
+    return ((c % CPR) ^ T::swz(row)) * 8;
+  };
 
   // TAIL = the K step that may run past K (only the last one, only when K % BK != 0):
   // chunks at k >= K are fetched from a zero buffer instead.
@@ -166,20 +166,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     for (int it = 0; it < LA; ++it) {
       const char* p;
       if constexpr (GATHER) {
-        const int k = k0 + a_col[it];
+        const int k = k0 + chunk_k(it);
         const int piece = min(k / kcw, g.gather_n - 1);
-        const int src = g.gather[(size_t)a_row[it] * g.gather_n + piece];
+        const int row = min((it * NT + tid) / CPR, g.M - 1 - m0);
+        const int src = g.gather[(size_t)(m0 + row) * g.gather_n + piece];
         p = (const char*)g.A + ((size_t)src * g.lda + (k - piece * kcw)) * 2;
       } else {
         p = ab + a_off[it];
       }
-      if constexpr (tail) { if (k0 + a_col[it] >= g.K) p = zeros; }
+      if constexpr (tail) { if (k0 + chunk_k(it) >= g.K) p = zeros; }
       __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(st + (it * NT + wave * 64) * 16), 16, 0, 0);
     }
 #pragma unroll
     for (int it = 0; it < LW; ++it) {
       const char* p = wb + w_off[it];
-      if constexpr (tail) { if (k0 + w_col[it] >= g.K) p = zeros; }
+      if constexpr (tail) { if (k0 + chunk_k(it) >= g.K) p = zeros; }
       __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(st + A_BYTES + (it * NT + wave * 64) * 16), 16, 0, 0);
     }
   };
