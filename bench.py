@@ -157,6 +157,15 @@ def main():
     if args.cpu_items > 0:
         cpu = cpu_baseline(cfg, gw, layers, patches, cu, grid, gpu_out, min(args.cpu_items, len(grids)))
 
+    # HBM-side bytes per launch of the dominant kernel come from rocprofv3 --pmc FETCH_SIZE /
+    # WRITE_SIZE runs of this same command (see profiles/); they cannot be collected in-process.
+    traffic = None
+    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "c2_bench_hbm_traffic.txt")
+    if args.config == "C2" and args.layers is None and os.path.exists(tfile):
+        for line in open(tfile):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == dom:
+                traffic = float(parts[2])
     res = {
         "metric": "visual tokens/sec (ViT encode fwd, 1 GPU) + MFMA util % of bf16 peak",
         "value": value, "unit": "visual tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -168,7 +177,7 @@ def main():
                    "tflops_end_to_end": flops_call / (ms_per_step * 1e-3) / 1e12,
                    "mfma_util_pct_end_to_end": 100 * flops_call / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "launches": dom_n, "avg_launch_ms": dom_ms / max(dom_n, 1),
                      "flops_per_launch": dom_work / max(dom_n, 1)},
         "cpu_baseline": cpu,

@@ -377,6 +377,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   } else {
     constexpr int ROWE = HALF * 4 + 16;
     constexpr int LPR4 = HALF / 4, RPS = NT / LPR4;    // lanes per row (4 columns each), rows per sweep
+    static_assert(BM % RPS == 0, "sweeps");
     const int cl = (tid % LPR4) * 4;                   // first of the lane's 4 columns inside the half
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -406,9 +407,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       }
       int pr = 0;
       if constexpr (EPI == EPI_QKV) pr = (n % g.head_dim) >> 1;   // even: two pairs = one 16-byte entry
-      for (int r = tid / LPR4; r < BM; r += RPS) {
+      // fully unrolled so that the residual loads / LDS reads of all sweeps are in flight together
+#pragma unroll
+      for (int sw = 0; sw < BM / RPS; ++sw) {
+        const int r = sw * RPS + tid / LPR4;
         const int m = m0 + r;
-        if (m >= g.M) break;
+        if (m >= g.M) continue;
         const float4 e = *(const float4*)(lds + r * ROWE + cl * 4);
         float v0 = e.x + b0, v1 = e.y + b1, v2 = e.z + b2, v3 = e.w + b3;
         if constexpr (EPI == EPI_QKV) {

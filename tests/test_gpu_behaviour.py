@@ -190,3 +190,39 @@ def test_c2_full_depth_batch_sampled_against_oracle():
         cu1, g1 = W.metadata([grids[item]])
         ref = O.encode(cfg, gw, layers, patches[784 * item:784 * (item + 1)], cu1, g1)
         check(cfg, got[196 * item:196 * (item + 1)], ref, "image %d of 8, 24 layers" % item)
+
+
+def test_empty_or_zero_sized_calls_are_rejected():
+    from paper_2601_11590_amd import binding as B
+    cfg = small("bf16")
+    enc, gw, layers = make_encoder(cfg, 64, segs=2, items=2)
+    try:
+        import torch
+        p = torch.zeros((4, cfg.patch_dim), dtype=torch.bfloat16, device="cuda:0")
+        out = torch.zeros((1, cfg.out_dim), dtype=torch.bfloat16, device="cuda:0")
+        import ctypes as C
+        cu = (C.c_int32 * 2)(0, 4)
+        grid = (C.c_int32 * 3)(1, 2, 2)
+        st = B.lib.epd_encode(enc.handle, p.data_ptr(), C.cast(cu, C.POINTER(C.c_int32)), 0,
+                              C.cast(grid, C.POINTER(C.c_int32)), 1, out.data_ptr(), None)
+        assert st == B.EPD_ERR_SHAPE
+        st = B.lib.epd_encode(enc.handle, p.data_ptr(), C.cast(cu, C.POINTER(C.c_int32)), 1,
+                              C.cast(grid, C.POINTER(C.c_int32)), 0, out.data_ptr(), None)
+        assert st == B.EPD_ERR_SHAPE
+        st = B.lib.epd_encode(enc.handle, None, C.cast(cu, C.POINTER(C.c_int32)), 1,
+                              C.cast(grid, C.POINTER(C.c_int32)), 1, out.data_ptr(), None)
+        assert st == B.EPD_ERR_INVALID_ARG
+        with pytest.raises(B.EpdError):
+            B.epd_encode_debug_hidden(enc.handle, out.data_ptr(), 0)   # no completed call yet
+    finally:
+        enc.close()
+
+
+def test_c3_full_varlen_batch_one_layer():
+    # all 32 images, 73 896 tokens (the maximum batch of the benchmark configurations), one layer
+    shaped_case(W.C3.replace(num_layers=1), W.grids_for(W.C3), "32 varlen images, 73896 tokens, L=1")
+
+
+def test_c4_full_sequence_one_layer():
+    # one 2688 x 2688 image: a single 28 224-token segment, head dim 72
+    shaped_case(W.C4.replace(num_layers=1), W.grids_for(W.C4), "28224-token single sequence, L=1")
