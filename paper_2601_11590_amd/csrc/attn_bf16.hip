@@ -95,8 +95,13 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   // K chunk beyond d); what they fetch only meets zero Q operands or unstored output rows
   __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE + (DB * 32 - DH) * 128 + 64];
 
-  const AttnWork w = a.work[blockIdx.x];
-  const int head = blockIdx.y;
+  // blocks are dealt round-robin to the 8 XCDs, each with its own L2: XCD x takes the x-th
+  // contiguous eighth of the (head, work item) list, so that the query tiles of one segment
+  // and head -- which read the same K and V^T -- run side by side behind one L2
+  const int nblk = gridDim.x;
+  const int vb = (blockIdx.x & 7) * (nblk >> 3) + min((int)(blockIdx.x & 7), nblk & 7) + (blockIdx.x >> 3);
+  const int head = vb / a.num_work;
+  const AttnWork w = a.work[vb - head * a.num_work];
   const int D = a.num_heads * DH;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -377,7 +382,7 @@ int attn_q_tile(bool bf16, int head_dim, int max_seg_len) {
 
 bool launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.num_work <= 0) return true;
-  dim3 grid(a.num_work, a.num_heads), block(256);
+  dim3 grid(a.num_work * a.num_heads), block(256);
   const int nq = a.q_tile / 128;
 #define EPD_ATTN(DH, MB2)                                                                    \
   case DH:                                                                                   \

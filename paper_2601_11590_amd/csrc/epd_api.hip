@@ -108,6 +108,10 @@ Layout make_layout(const epd_encode_cfg& c) {
   const size_t S = c.max_segments, I = c.max_items;
   L.meta_bytes = align_up(((S + 1) * 2 + (I + 1) * 2 + 3 * I + 4 * (size_t)L.max_work) * 4);
   L.meta = take(L.meta_bytes);
+  // The bf16 GEMMs fetch whole 256-row operand tiles without clamping rows at the edge of a
+  // matrix (what lies beyond only feeds accumulators that are never stored); this tail keeps
+  // such reads, from whichever buffer they start, inside the workspace.
+  if (bf) take(256 * std::max(std::max(D, F), (size_t)L.mm * D) * es);
   L.total = off;
   return L;
 }
@@ -447,6 +451,8 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
   auto gemm = [&](int step, GemmArgs& g) {
     StepTimer tm(h, step, 2.0 * g.M * (double)g.N * g.K, st);
     g.zeros = h->ws + L.zeros;
+    // operands that live in the workspace may be read past their last row (see make_layout)
+    g.overread_ok = (g.A != packed_patches && !g.gather) ? 1 : 0;
     if (bf) launch_gemm_bf16(g, st); else launch_gemm_f32(g, st);
   };
   auto norm = [&](const void* gma, const void* bta, void* dst) {

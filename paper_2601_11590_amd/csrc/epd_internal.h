@@ -44,13 +44,17 @@ struct GemmArgs {
   int vt_stride;
   const int32_t* vcol;  // [M] column of token m in vt
   const void* zeros;    // bf16 path: >= 16 readable zero bytes (source of out-of-range tile chunks)
+  int overread_ok;      // bf16 path: 1 = rows [M, round_up(M, 256)) of A and [N, round_up(N, 256)) of
+                        //   W are readable memory (contents irrelevant): enables the load path
+                        //   without per-lane row clamping
   int tile_cfg;         // bf16 path: 0 = automatic choice, k > 0 = tile variant k - 1 (tuning)
   int group_m;          // bf16 path: row tiles per rasterisation group (set by the launcher)
   unsigned long long* trace;  // tuning builds only (EPD_GEMM_TRACE): per-wave stall cycle counters
 };
 
 // ---------------------------------------------------------------- attention description
-// One work item = one tile of query rows of one segment (all heads via gridDim.y).
+// One work item = one tile of query rows of one segment; the grid holds one block per
+// (head, work item).
 struct AttnWork { int32_t q0, seg_start, seg_len, vcol0; };
 
 struct AttnArgs {

@@ -47,20 +47,22 @@ __device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d)
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 
-// x * Phi(x) with the Gaussian CDF through the complementary error function in the
-// rational-exponential form of the Handbook of Mathematical Functions, 7.1.26 (absolute
-// error of erf below 1.5e-7, far below the bf16 rounding of the result):
-//   h = erfc(|x|/sqrt2) / 2,   gelu(x) = max(x, 0) - |x| h.
+// x * Phi(x) with the Gaussian CDF written through its upper tail,
+//   gelu(x) = max(x, 0) - |x| Q(|x|),   Q(a) = erfc(a / sqrt2) / 2 = 2^(a P(a) - 1),
+// where P is a degree-5 polynomial fitted (weighted minimax, a in [0, 7.5]) to
+// log2(erfc(a / sqrt2)) / a.  The logarithm of the tail is smooth, so one v_exp_f32 and six
+// fused multiply-adds reach an absolute error below 2e-6 and a relative error below 1.5e-3 even
+// where gelu is of order 1e-12 -- both far below the bf16 rounding of the stored result.
+// Beyond a = 7.5 the tail term is below 1e-12 and the exponent is simply held.
 __device__ __forceinline__ float gelu_erf_fast(float x) {
-  const float ax = fabsf(x);
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, ax, 1.0f));
-  float p = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
-  p = fmaf(p, t, 0.5f * 1.421413741f);
-  p = fmaf(p, t, 0.5f * -0.284496736f);
-  p = fmaf(p, t, 0.5f * 0.254829592f);
-  p *= t;
-  const float e = __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.44269504088896340736f));
-  return fmaf(-ax, p * e, fmaxf(x, 0.f));
+  const float a = fminf(fabsf(x), 7.5f);
+  float p = fmaf(2.3815253741819458e-05f, a, -0.0006414791230697928f);
+  p = fmaf(p, a, 0.007484599623650507f);
+  p = fmaf(p, a, -0.05223089570546575f);
+  p = fmaf(p, a, -0.459768916243223f);
+  p = fmaf(p, a, -1.1509091680606687f);
+  const float e = __builtin_amdgcn_exp2f(fmaf(p, a, -1.0f));
+  return fmaf(-fabsf(x), e, fmaxf(x, 0.f));
 }
 
 __device__ __forceinline__ float gelu_tanh_fast(float x) {
@@ -79,10 +81,11 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 template <int OFF> __device__ __forceinline__ void ds_read_b128(bf16x8& d, uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
 }
-template <int N, int STRIDE, int I = 0> __device__ __forceinline__ void ds_read_rows(bf16x8* d, uint32_t addr) {
+template <int N, int STRIDE, int BASE, int I = 0> __device__ __forceinline__ void ds_read_rows(bf16x8* d, uint32_t addr) {
   if constexpr (I < N) {
-    ds_read_b128<I * STRIDE>(d[I], addr);
-    ds_read_rows<N, STRIDE, I + 1>(d, addr);
+    static_assert(BASE + I * STRIDE < 65536, "LDS offset field");
+    ds_read_b128<BASE + I * STRIDE>(d[I], addr);
+    ds_read_rows<N, STRIDE, BASE, I + 1>(d, addr);
   }
 }
 // wait until at most PENDING LDS reads of this wave are outstanding (they return in order),
@@ -114,12 +117,12 @@ struct Tile {
   __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 };
 
-template <class T, int EPI, int OUT, bool VMODE, bool GATHER>
+template <class T, int EPI, int OUT, bool VMODE, bool GATHER, bool FAST>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const int n0, char* const lds) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, WM = T::WM, WN = T::WN, TM = T::TM, TN = T::TN;
   constexpr int CPR = T::CPR, LA = T::LA, LW = T::LW;
   constexpr int ROWB = BK * 2;               // bytes per tile row
-  constexpr int A_BYTES = BM * ROWB;
+  constexpr int A_BYTES = BM * ROWB, W_BYTES = BN * ROWB;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -132,22 +135,29 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
 
   // ---- per-thread load descriptors.  Load instruction `it` of a stage covers LDS chunks
   // it*NT + wave*64 + lane; chunk c is row c / CPR, slot c % CPR, and holds k-chunk
-  // slot ^ swz(row) of that row.  Rows beyond M (or N) are clamped to the last valid row:
-  // they only feed accumulators that are never stored.  Addresses are a block-uniform base
-  // (advanced once per K step) plus a loop-invariant 32-bit per-lane byte offset.
+  // slot ^ swz(row) of that row.  One instruction covers RPP = NT / CPR rows (a multiple of
+  // 16, so the swizzle of a lane's row is the same for every `it`).
+  //   FAST (the caller guarantees that whole tiles of A and W may be read, also where they
+  //   run past M or N, and K is a multiple of BK): the address is a wave-uniform row base,
+  //   advanced with scalar arithmetic, plus ONE per-lane offset for all loads of an operand.
+  //   Otherwise rows beyond M (or N) are clamped to the last valid row -- they only feed
+  //   accumulators that are never stored -- and every load keeps its own per-lane offset.
+  constexpr int RPP = NT / CPR;
+  static_assert(RPP % 16 == 0, "rows per load instruction");
   const char* a_base_ptr = (const char*)g.A + (size_t)m0 * g.lda * 2;
   const int ldw = g.ldw ? g.ldw : g.K;
   const char* w_base_ptr = (const char*)g.W + (size_t)n0 * ldw * 2;
-  uint32_t a_off[LA], w_off[LW];
+  constexpr int NOFF_A = FAST ? 1 : LA, NOFF_W = FAST ? 1 : LW;
+  uint32_t a_off[NOFF_A], w_off[NOFF_W];
 #pragma unroll
-  for (int it = 0; it < LA; ++it) {
+  for (int it = 0; it < NOFF_A; ++it) {
     const int c = it * NT + tid, row = c / CPR, col = (c % CPR) ^ T::swz(row);
-    a_off[it] = (uint32_t)min(row, g.M - 1 - m0) * (uint32_t)g.lda * 2u + col * 16;
+    a_off[it] = (uint32_t)(FAST ? row : min(row, g.M - 1 - m0)) * (uint32_t)g.lda * 2u + col * 16;
   }
 #pragma unroll
-  for (int it = 0; it < LW; ++it) {
+  for (int it = 0; it < NOFF_W; ++it) {
     const int c = it * NT + tid, row = c / CPR, col = (c % CPR) ^ T::swz(row);
-    w_off[it] = (uint32_t)min(row, g.N - 1 - n0) * (uint32_t)ldw * 2u + col * 16;
+    w_off[it] = (uint32_t)(FAST ? row : min(row, g.N - 1 - n0)) * (uint32_t)ldw * 2u + col * 16;
   }
   // first k of the chunk that load instruction `it` fetches (only the ragged-K and gather paths
   // need it, so it is recomputed there rather than kept in registers)
@@ -158,8 +168,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
 
   // TAIL = the K step that may run past K (only the last one, only when K % BK != 0):
   // chunks at k >= K are fetched from a zero buffer instead.
-  auto issue = [&](auto TAIL, char* st, int k0) {
+  // LDS: [A stage 0 | A stage 1 | W stage 0 | W stage 1]
+  auto issue = [&](auto TAIL, int stage, int k0) {
     constexpr bool tail = decltype(TAIL)::value;
+    char* const sa = lds + stage * A_BYTES;
+    char* const sw = lds + 2 * A_BYTES + stage * W_BYTES;
     const char* ab = a_base_ptr + (size_t)k0 * 2;
     const char* wb = w_base_ptr + (size_t)k0 * 2;
 #pragma unroll
@@ -171,24 +184,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         const int row = min((it * NT + tid) / CPR, g.M - 1 - m0);
         const int src = g.gather[(size_t)(m0 + row) * g.gather_n + piece];
         p = (const char*)g.A + ((size_t)src * g.lda + (k - piece * kcw)) * 2;
+      } else if constexpr (FAST) {
+        p = ab + (size_t)(it * RPP) * (size_t)g.lda * 2 + a_off[0];
       } else {
         p = ab + a_off[it];
       }
       if constexpr (tail) { if (k0 + chunk_k(it) >= g.K) p = zeros; }
-      __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(st + (it * NT + wave * 64) * 16), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(sa + (it * NT + wave * 64) * 16), 16, 0, 0);
     }
 #pragma unroll
     for (int it = 0; it < LW; ++it) {
-      const char* p = wb + w_off[it];
+      const char* p;
+      if constexpr (FAST) p = wb + (size_t)(it * RPP) * (size_t)ldw * 2 + w_off[0];
+      else p = wb + w_off[it];
       if constexpr (tail) { if (k0 + chunk_k(it) >= g.K) p = zeros; }
-      __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(st + A_BYTES + (it * NT + wave * 64) * 16), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(sw + (it * NT + wave * 64) * 16), 16, 0, 0);
     }
   };
   const int nk = (g.K + BK - 1) / BK;
   const bool ragged_k = (g.K % BK) != 0;
-  auto issue_step = [&](char* st, int kt) {      // kt < nk
-    if (ragged_k && kt == nk - 1) issue(std::true_type{}, st, kt * BK);
-    else issue(std::false_type{}, st, kt * BK);
+  auto issue_step = [&](int stage, int kt) {      // kt < nk
+    if constexpr (FAST) {
+      issue(std::false_type{}, stage, kt * BK);
+    } else {
+      if (ragged_k && kt == nk - 1) issue(std::true_type{}, stage, kt * BK);
+      else issue(std::false_type{}, stage, kt * BK);
+    }
   };
 
   f32x16 acc[TM][TN];
@@ -207,20 +228,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   constexpr int KS = BK / 16, NF = TM + TN;
   constexpr bool LATE_REFILL = TM * TN <= 4;
   const uint32_t lds0 = (uint32_t)(size_t)EPD_LPTR(lds);
-  uint32_t a_rd[2][KS], w_rd[2][KS];
-#pragma unroll
-  for (int st = 0; st < 2; ++st)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int off = ((ks * 2 + lg) ^ T::swz(l32)) * 16;
-      a_rd[st][ks] = lds0 + st * T::STAGE_BYTES + (wm * WM + l32) * ROWB + off;
-      w_rd[st][ks] = lds0 + st * T::STAGE_BYTES + A_BYTES + (wn * WN + l32) * ROWB + off;
-    }
+  // Address of slice ks = address of slice 0 with bits 5.. of the chunk slot flipped (the row
+  // base has zeros there); stage and 32-row block go into the instruction's offset field.
+  const uint32_t a_rd0 = lds0 + (wm * WM + l32) * ROWB + ((lg ^ T::swz(l32)) * 16);
+  const uint32_t w_rd0 = lds0 + 2 * A_BYTES + (wn * WN + l32) * ROWB + ((lg ^ T::swz(l32)) * 16);
   bf16x8 frag[2][NF];
   auto read_frags = [&](auto BUF, auto ST, auto KSTEP) {
     constexpr int buf = decltype(BUF)::value, st = decltype(ST)::value, ks = decltype(KSTEP)::value;
-    ds_read_rows<TM, 32 * ROWB>(&frag[buf][0], a_rd[st][ks]);
-    ds_read_rows<TN, 32 * ROWB>(&frag[buf][TM], w_rd[st][ks]);
+    ds_read_rows<TM, 32 * ROWB, st * A_BYTES>(&frag[buf][0], a_rd0 ^ (uint32_t)(ks * 32));
+    ds_read_rows<TN, 32 * ROWB, st * W_BYTES>(&frag[buf][TM], w_rd0 ^ (uint32_t)(ks * 32));
   };
   auto wait_frags = [&](auto BUF, auto PENDING) {
     wait_lds_reads<decltype(PENDING)::value, NF>(&frag[decltype(BUF)::value][0]);
@@ -254,10 +270,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   unsigned long long tr_vm = 0, tr_bar = 0;
   const unsigned long long tr_start = __builtin_readcyclecounter();
 #endif
-  issue_step(lds, 0);
+  issue_step(0, 0);
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
-  if (nk > 1 && !(g.tile_cfg & 256)) issue_step(lds + T::STAGE_BYTES, 1);
+  if (nk > 1 && !(g.tile_cfg & 256)) issue_step(1, 1);
   read_frags(I0{}, I0{}, I0{});
 
   auto step = [&](auto S, int kt) {
@@ -288,7 +304,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
           if (!(g.tile_cfg & 512)) __builtin_amdgcn_s_barrier();
 #endif
           if constexpr (!LATE_REFILL) {
-            if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(lds + s * T::STAGE_BYTES, kt + 2);
+            if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(s, kt + 2);
           }
           read_frags(I0{}, SN{}, I0{});
         } else {
@@ -300,7 +316,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
           // address arithmetic and load instructions run in their shadow (pinning this order
           // costs registers, which the large wave tiles do not have)
           __builtin_amdgcn_sched_barrier(0);
-          if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(lds + s * T::STAGE_BYTES, kt + 2);
+          if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(s, kt + 2);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -469,7 +485,7 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
   tm = first + (local - tn * rows);
 }
 
-template <class T, int EPI, int OUT, bool GATHER>
+template <class T, int EPI, int OUT, bool GATHER, bool FAST>
 __global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(1024))) char lds[T::LDS_BYTES];
   const int tiles_n = (g.N + T::BN - 1) / T::BN, tiles_m = (g.M + T::BM - 1) / T::BM;
@@ -478,11 +494,11 @@ __global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g)
   const int m0 = tm * T::BM, n0 = tn * T::BN;
   if constexpr (EPI == EPI_QKV) {
     if (n0 >= g.qk_cols) {
-      gemm_tile<T, EPI, OUT, true, false>(g, m0, n0, lds);
+      gemm_tile<T, EPI, OUT, true, false, FAST>(g, m0, n0, lds);
       return;
     }
   }
-  gemm_tile<T, EPI, OUT, false, GATHER>(g, m0, n0, lds);
+  gemm_tile<T, EPI, OUT, false, GATHER, FAST>(g, m0, n0, lds);
 }
 
 template <class T, int EPI, int OUT, bool GATHER>
@@ -495,16 +511,19 @@ static void launch_cfg(const GemmArgs& g, hipStream_t s) {
     a.group_m = (int)std::max(1L, std::min((long)tiles_m, (2L << 20) / std::max(panel, 1L)));
   }
   a.group_m = std::min(a.group_m, tiles_m);
-  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, GATHER>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
+  if constexpr (!GATHER) {
+    if (g.overread_ok && g.K % T::BK == 0) {
+      hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, false, true>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
+      return;
+    }
+  }
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, GATHER, false>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
 }
 
 //            BM   BN  BK  WM WN MINBLK
-using T0 = Tile<256, 256, 64, 2, 4, 1>;   // 8 waves, 128x64 wave tiles, 128 KB LDS
-using T1 = Tile<256, 256, 64, 2, 2, 1>;   // 4 waves, 128x128 wave tiles
-using T2 = Tile<256, 128, 64, 2, 2, 1>;   // 96 KB LDS
-using T3 = Tile<128, 256, 64, 2, 2, 1>;
-using T4 = Tile<128, 128, 64, 2, 2, 2>;   // 64 KB LDS, two blocks per CU
-using T5 = Tile<256, 128, 32, 2, 2, 2>;   // 48 KB LDS, two blocks per CU
+using T0 = Tile<256, 256, 64, 2, 4, 1>;   // 8 waves, 128x64 wave tiles, 128 KB LDS, one block per CU
+using T2 = Tile<256, 128, 64, 2, 2, 1>;   // 4 waves, 128x64 wave tiles, 96 KB LDS
+using T4 = Tile<128, 128, 64, 2, 2, 2>;   // 4 waves, 64x64 wave tiles, 64 KB LDS, two blocks per CU
 
 static int forced_tile() {
   static int t = [] {
@@ -514,23 +533,36 @@ static int forced_tile() {
   return t;
 }
 
-// Tile choice: the 256 x 256 tile halves the operand traffic per flop and wins once there are
-// several rounds of tiles per compute unit; small grids quantise better with 128 x 128 tiles,
-// two blocks per compute unit.
+static int num_cus() {
+  static int n = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    return v;
+  }();
+  return n;
+}
+
+// Tile choice.  The 256 x 256 tile halves the operand traffic per flop and is the faster
+// main loop, but runs one block per compute unit; the 128 x 128 tile runs two, which hides
+// the epilogue of one block behind the main loop of the other and quantises better on small
+// grids.  Both are priced by the fraction of block slots their last round of tiles leaves
+// idle, and the large tile is taken unless it loses clearly on that count.
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
   int t = (g.tile_cfg & 255) > 0 ? (g.tile_cfg & 255) - 1 : forced_tile();
-  if (t < 0) {
-    const long big_tiles = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-    t = big_tiles >= 1024 ? 0 : 4;
+  if (t != 0 && t != 2 && t != 4) {
+    const long n0 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+    const long n4 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128);
+    const long s0 = num_cus(), s4 = 2L * num_cus();
+    const double eff0 = (double)n0 / (double)((n0 + s0 - 1) / s0 * s0);
+    const double eff4 = (double)n4 / (double)((n4 + s4 - 1) / s4 * s4);
+    t = (n0 >= 4 * s0 || eff0 >= 0.95 * eff4) ? 0 : 4;
   }
-  if (EPI == EPI_QKV && (t == 0 || t == 1 || t == 3) && g.qk_cols % 256 != 0) t = 2;
+  if (EPI == EPI_QKV && t == 0 && g.qk_cols % 256 != 0) t = 2;
   switch (t) {
     case 0: launch_cfg<T0, EPI, OUT, GATHER>(g, s); break;
-    case 1: launch_cfg<T1, EPI, OUT, GATHER>(g, s); break;
     case 2: launch_cfg<T2, EPI, OUT, GATHER>(g, s); break;
-    case 3: launch_cfg<T3, EPI, OUT, GATHER>(g, s); break;
-    case 5: launch_cfg<T5, EPI, OUT, GATHER>(g, s); break;
     default: launch_cfg<T4, EPI, OUT, GATHER>(g, s); break;
   }
 }
