@@ -164,7 +164,7 @@ def main():
     if args.config == "C2" and args.layers is None and os.path.exists(tfile):
         for line in open(tfile):
             parts = line.split()
-            if len(parts) == 3 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == dom:
+            if len(parts) >= 3 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == dom:
                 traffic = float(parts[2])
     res = {
         "metric": "visual tokens/sec (ViT encode fwd, 1 GPU) + MFMA util % of bf16 peak",

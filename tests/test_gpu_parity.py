@@ -81,6 +81,13 @@ def test_bf16_frame_segments_and_sharp_softmax():
     parity(small("bf16"), RAGGED, q_gain=16.0, std=0.05)
 
 
+@pytest.mark.parametrize("act", ["gelu_erf", "gelu_tanh"])
+def test_bf16_wide_activation_range(act):
+    # large weights drive the MLP pre-activations far into both GELU tails (|x| up to ~15),
+    # where the kernel's approximations of the activation must still follow the exact function
+    parity(small("bf16", num_layers=1, act=act), RAGGED, std=0.2)
+
+
 def test_bf16_many_tiles():
     # > 2 row tiles of every GEMM, attention segments with several query and key tiles
     parity(small("bf16", num_layers=3), [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8)])
