@@ -78,22 +78,26 @@ __device__ __forceinline__ float half_swap_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int DH, int NQ, int MINBLK>
+template <int DH, int NQ, int MINBLK, bool SUMROW>
 __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   constexpr int KS = (DH + 15) / 16;       // k-steps of the score GEMM
-  constexpr int DB = (DH + 31) / 32;       // 32-row blocks of O^T
+  constexpr int DB = (DH + 31) / 32;       // 32-row blocks of O^T that hold output channels
+  // SUMROW: row DH of the V^T tile in LDS is a row of ones, so that row DH of O^T accumulates
+  // the softmax denominator in the matrix cores (rescaled together with the outputs) instead
+  // of 32 vector additions per key tile
+  constexpr int DBX = SUMROW ? (DH + 32) / 32 : DB;   // 32-row blocks of O^T that are computed
   constexpr int CPRK = DH / 8;             // 16-byte chunks per K row
   constexpr int ROWK = DH * 2;             // bytes per K row in LDS
   constexpr int KBYTES = BKV * ROWK;
-  constexpr int VBYTES = DH * 128;         // V^T tile: DH rows of 64 keys
+  constexpr int VBYTES = DBX * 32 * 128;   // V^T tile: DH rows of 64 keys, padded to whole 32-row blocks
   constexpr int STAGE = KBYTES + VBYTES;
   constexpr int LK = (BKV * CPRK + 255) / 256, LV = (DH * 8 + 255) / 256;
   // K row swizzle: power-of-two rows need one (all rows would start in the same banks);
   // 144-byte rows (d = 72) already spread 16 consecutive rows over all 64 banks
   constexpr bool SWZK = (CPRK & (CPRK - 1)) == 0;
-  // slack: fragment reads of padded head dims run past the tile (V^T rows up to DB*32, the
-  // K chunk beyond d); what they fetch only meets zero Q operands or unstored output rows
-  __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE + (DB * 32 - DH) * 128 + 64];
+  // slack: the K fragment read of a padded head dim runs one chunk past the tile; what it
+  // fetches only meets zero Q operands
+  __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE + 64];
 
   // blocks are dealt round-robin to the 8 XCDs, each with its own L2: XCD x takes the x-th
   // contiguous eighth of the (head, work item) list, so that the query tiles of one segment
@@ -111,6 +115,17 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   const char* kbase = (const char*)(qk + (size_t)w.seg_start * a.ld_qkv + D + head * DH);
   const char* vbase = (const char*)((const uint16_t*)a.vt + (size_t)head * DH * a.vt_stride + w.vcol0);
   const int ntiles = (w.seg_len + BKV - 1) / BKV;
+
+  // V^T rows DH .. DBX*32-1 of both stages are never loaded: row DH becomes the row of ones
+  // (SUMROW), the others zero, once, before the first barrier
+  if constexpr (DBX * 32 > DH) {
+    constexpr int PADCH = (DBX * 32 - DH) * 8;   // 16-byte chunks per stage
+    for (int i = threadIdx.x; i < 2 * PADCH; i += 256) {
+      const int st = i / PADCH, ch = i - st * PADCH;
+      const uint32_t fill = (SUMROW && ch < 8) ? 0x3F803F80u : 0u;   // bf16 1.0 pairs
+      *(uint4*)(lds + st * STAGE + KBYTES + DH * 128 + ch * 16) = make_uint4(fill, fill, fill, fill);
+    }
+  }
 
   // ---- load descriptors (direct-to-LDS: lane i of an instruction fills LDS chunk base + i)
   int k_row[LK], k_ch[LK];
@@ -181,9 +196,9 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     }
   }
 
-  f32x16 o[DB][NQ];
+  f32x16 o[DBX][NQ];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int db = 0; db < DBX; ++db)
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
@@ -267,17 +282,17 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
           for (int e = 0; e < 8; e += 2) {
             const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][8 * mm + e], c, -mnew));
             const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][8 * mm + e + 1], c, -mnew));
-            psum += p0 + p1;
+            if constexpr (!SUMROW) psum += p0 + p1;
             pb[nq][kb][mm].w[e >> 1] = pack2(p0, p1);
           }
-      lrun[nq] = lrun[nq] * alpha[nq] + psum;
+      if constexpr (!SUMROW) lrun[nq] = lrun[nq] * alpha[nq] + psum;
     }
     // rescale the output accumulators only if some row's maximum moved (wave-uniform test)
     if (__builtin_amdgcn_ballot_w64(moved) != 0) {
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DBX; ++db)
 #pragma unroll
           for (int v = 0; v < 16; ++v) o[db][nq][v] *= alpha[nq];
     }
@@ -301,21 +316,16 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
           o[db][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[buf][f].v, pb[nq][f >> 1][f & 1].v, o[db][nq], 0, 0, 0);
       }
     };
+    auto pv_blocks = [&](auto self, auto DBI) {
+      constexpr int db = decltype(DBI)::value;
+      if constexpr (db < DBX) {
+        if constexpr (db + 1 < DBX) { read_v(std::integral_constant<int, db + 1>{}, (db + 1) & 1); lds_wait<8>(); } else { lds_wait<0>(); }
+        pv(db, db & 1);
+        self(self, std::integral_constant<int, db + 1>{});
+      }
+    };
     read_v(std::integral_constant<int, 0>{}, 0);
-    if constexpr (DB > 1) { read_v(std::integral_constant<int, 1>{}, 1); lds_wait<8>(); } else { lds_wait<0>(); }
-    pv(0, 0);
-    if constexpr (DB > 1) {
-      if constexpr (DB > 2) { read_v(std::integral_constant<int, 2>{}, 0); lds_wait<8>(); } else { lds_wait<0>(); }
-      pv(1, 1);
-    }
-    if constexpr (DB > 2) {
-      if constexpr (DB > 3) { read_v(std::integral_constant<int, 3>{}, 1); lds_wait<8>(); } else { lds_wait<0>(); }
-      pv(2, 0);
-    }
-    if constexpr (DB > 3) {
-      lds_wait<0>();
-      pv(3, 1);
-    }
+    pv_blocks(pv_blocks, std::integral_constant<int, 0>{});
   };
 
   // ---- key tiles: two-stage ring, the next tile is in flight while this one is multiplied
@@ -338,7 +348,17 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     const int qrow = q_wave0 + nq * 32 + l32;
-    const float ltot = half_swap_sum(lrun[nq]);
+    float ltot;
+    if constexpr (SUMROW) {
+      // row DH of O^T: block DH / 32, row r = DH % 32 -> accumulator register 4*(r/8) + r%4 of
+      // the lanes of half (r % 8) / 4; the swap hands both halves' values to every lane
+      constexpr int r = DH % 32;
+      const float x = o[DH / 32][nq][4 * (r / 8) + (r % 4)];
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+      ltot = __uint_as_float(sw[(r % 8) / 4]);
+    } else {
+      ltot = half_swap_sum(lrun[nq]);
+    }
     if (qrow >= seg_end) continue;
     const float inv = 1.0f / ltot;
 #pragma unroll
@@ -384,11 +404,16 @@ bool launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.num_work <= 0) return true;
   dim3 grid(a.num_work * a.num_heads), block(256);
   const int nq = a.q_tile / 128;
-#define EPD_ATTN(DH, MB2)                                                                    \
-  case DH:                                                                                   \
-    if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, MB2>), grid, block, 0, s, a);   \
-    else hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, 2>), grid, block, 0, s, a);             \
-    return true
+  // The row of ones is used where the head dim leaves spare rows in its last 32-row block of
+  // O^T (d = 72, 80: +3 % measured); for d = 32, 64, 96, 128 it would add a block of matrix
+  // instructions and measured 2-7 % slower.
+#define EPD_ATTN(DH, MB2)                                                                                \
+  case DH: {                                                                                             \
+    constexpr bool sr = (DH % 32) != 0;                                                                  \
+    if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, MB2, sr>), grid, block, 0, s, a);           \
+    else hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, 2, sr>), grid, block, 0, s, a);                     \
+    return true;                                                                                         \
+  }
   switch (a.head_dim) {
     EPD_ATTN(32, 2);
     EPD_ATTN(64, 2);
