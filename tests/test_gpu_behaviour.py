@@ -226,3 +226,29 @@ def test_c3_full_varlen_batch_one_layer():
 def test_c4_full_sequence_one_layer():
     # one 2688 x 2688 image: a single 28 224-token segment, head dim 72
     shaped_case(W.C4.replace(num_layers=1), W.grids_for(W.C4), "28224-token single sequence, L=1")
+
+
+def test_c5_full_video_batch_one_layer_last_clip_against_oracle():
+    """All four 8 x 32 x 32 clips (32 768 tokens, hidden 3200, 25 x 128 heads, 3-D rotary) in one
+    call, one layer; the oracle recomputes the last clip alone (8192-token segment), which
+    block-diagonal attention makes equal to its rows in the batch."""
+    from paper_2601_11590_amd import binding as B
+    import torch
+    cfg = W.C5.replace(num_layers=1)
+    grids = W.grids_for(W.C5)
+    log("case %s: 4 clips, 32768 tokens, L=1; oracle on the last clip" % cfg.name)
+    gw, layers = W.all_weights(cfg)
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids)
+    enc = B.EpdEncoder(cfg, gw, layers, max_tokens=patches.shape[0], max_segments=len(grids), max_items=len(grids))
+    try:
+        got = enc.encode(B.to_device_patches(patches, cfg.dtype), cu, grid)
+        torch.cuda.synchronize()
+        got = got.float().cpu().numpy()
+    finally:
+        enc.close()
+    n, nm = W.num_tokens(grids[:1]), W.num_merged_tokens(grids[:1], cfg.merge)
+    assert got.shape == (4 * nm, cfg.out_dim) and np.isfinite(got).all()
+    cu1, g1 = W.metadata(grids[3:])
+    ref = O.encode(cfg, gw, layers, patches[3 * n:], cu1, g1)
+    check(cfg, got[3 * nm:], ref, "clip 4 of 4, 8192 tokens")
