@@ -44,7 +44,9 @@ struct Layout {
   int pdim, pairs, mm, max_tm, max_work, vt_stride;
   size_t patch_w, patch_b, final_g, final_b, merge_w, merge_b;
   std::vector<LayerW> layers;
-  size_t x, xn, qkv, vt, o, hd, rot, merge_idx, vcol, pair_freq, pair_axis, zeros, meta;
+  size_t x, xn, qkv, vt, o, hd, rot, merge_idx, vcol, pair_freq, pair_axis, zeros, meta, stats;
+  bool fold_rms;     // RMSNorm of the blocks folded into the GEMMs around it (bf16 path)
+  int stats_n;       // 128-column segments per residual row
   size_t meta_bytes, total;
 };
 
@@ -108,6 +110,13 @@ Layout make_layout(const epd_encode_cfg& c) {
   const size_t S = c.max_segments, I = c.max_items;
   L.meta_bytes = align_up(((S + 1) * 2 + (I + 1) * 2 + 3 * I + 4 * (size_t)L.max_work) * 4);
   L.meta = take(L.meta_bytes);
+  // bf16 + RMSNorm + hidden a multiple of 128: the block norms are not run as kernels.  The
+  // residual GEMMs leave the raw rows in bf16 (in the Xn buffer) and their sums of squares per
+  // 128-column segment; the consuming GEMM scales its accumulator rows by the resulting
+  // 1/rms, gamma being folded into its weights at create.
+  L.fold_rms = bf && c.norm == EPD_RMSNORM && c.hidden % 128 == 0 && c.num_layers > 0;
+  L.stats_n = c.hidden / 128;
+  L.stats = take(T * (size_t)std::max(L.stats_n, 1) * 4, L.fold_rms);
   // The bf16 GEMMs fetch whole 256-row operand tiles without clamping rows at the edge of a
   // matrix (what lies beyond only feeds accumulators that are never stored); this tail keeps
   // such reads, from whichever buffer they start, inside the workspace.
@@ -311,6 +320,12 @@ epd_status epd_encode_create(const epd_encode_cfg* cfg, epd_handle* out) {
     EPD_CW(d.fc1_b, s.fc1_b, F * es);
     EPD_CW(d.fc2_w, s.fc2_w, D * F * es);
     EPD_CW(d.fc2_b, s.fc2_b, D * es);
+    if (L.fold_rms) {
+      // norm2 -> fc1 in every block; norm1 -> qkv from the second block on (the first block's
+      // norm1 follows the patch embedding and runs as a kernel)
+      launch_fold_gamma(h->ws + d.fc1_w, h->ws + d.norm2_g, (int)F, (int)D, 0);
+      if (l > 0) launch_fold_gamma(h->ws + d.qkv_w, h->ws + d.norm1_g, 3 * (int)D, (int)D, 0);
+    }
   }
 #undef EPD_CW
   // rotary frequencies per pair (double) and the axis each pair belongs to
@@ -466,11 +481,20 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
     g.M = T; g.N = D; g.K = L.pdim; g.epilogue = EPI_STORE; g.out = X; g.ldo = D; g.out_f32 = 1;
     gemm(EPD_STEP_PATCH_EMBED, g);
   }
+  float* stats = L.fold_rms ? h->at<float>(L.stats) : nullptr;
+  auto consume_stats = [&](GemmArgs& g) {   // A = raw bf16 rows, scale 1/rms applied in the epilogue
+    g.stats_in = stats; g.stats_n = L.stats_n; g.stats_inv_dim = 1.0f / (float)D; g.stats_eps = c.norm_eps;
+  };
+  auto produce_stats = [&](GemmArgs& g) {   // residual GEMM also leaves bf16 rows + sums of squares
+    g.xb = Xn; g.ldxb = D; g.stats_out = stats; g.stats_n = L.stats_n;
+  };
   for (int l = 0; l < c.num_layers; ++l) {
     const LayerW& w = L.layers[l];
-    norm(h->at<void>(w.norm1_g), h->at<void>(w.norm1_b), Xn);
+    const bool fold1 = L.fold_rms && l > 0;
+    if (!fold1) norm(h->at<void>(w.norm1_g), h->at<void>(w.norm1_b), Xn);
     {  // QKV projection, rotary on Q and K in the epilogue
       GemmArgs g{};
+      if (fold1) consume_stats(g);
       g.A = Xn; g.lda = D; g.W = h->at<void>(w.qkv_w); g.bias = h->at<void>(w.qkv_b);
       g.M = T; g.N = 3 * D; g.K = D; g.epilogue = EPI_QKV; g.out = QKV; g.ldo = bf ? 2 * D : 3 * D;
       g.rot = rot; g.rot_pairs = L.pairs; g.head_dim = c.head_dim; g.qk_cols = 2 * D;
@@ -492,11 +516,13 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
       GemmArgs g{};
       g.A = O; g.lda = D; g.W = h->at<void>(w.proj_w); g.bias = h->at<void>(w.proj_b);
       g.M = T; g.N = D; g.K = D; g.epilogue = EPI_RESIDUAL; g.resid = X; g.ldr = D;
+      if (L.fold_rms) produce_stats(g);
       gemm(EPD_STEP_PROJ, g);
     }
-    norm(h->at<void>(w.norm2_g), h->at<void>(w.norm2_b), Xn);
+    if (!L.fold_rms) norm(h->at<void>(w.norm2_g), h->at<void>(w.norm2_b), Xn);
     {  // Hd = GELU(Xn W1^T + b1)
       GemmArgs g{};
+      if (L.fold_rms) consume_stats(g);
       g.A = Xn; g.lda = D; g.W = h->at<void>(w.fc1_w); g.bias = h->at<void>(w.fc1_b);
       g.M = T; g.N = F; g.K = D; g.epilogue = EPI_GELU; g.act = c.act; g.out = Hd; g.ldo = F;
       gemm(EPD_STEP_FC1, g);
@@ -505,6 +531,7 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
       GemmArgs g{};
       g.A = Hd; g.lda = F; g.W = h->at<void>(w.fc2_w); g.bias = h->at<void>(w.fc2_b);
       g.M = T; g.N = D; g.K = F; g.epilogue = EPI_RESIDUAL; g.resid = X; g.ldr = D;
+      if (L.fold_rms && l + 1 < c.num_layers) produce_stats(g);
       gemm(EPD_STEP_FC2, g);
     }
   }

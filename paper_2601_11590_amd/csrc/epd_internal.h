@@ -47,6 +47,17 @@ struct GemmArgs {
   int overread_ok;      // bf16 path: 1 = rows [M, round_up(M, 256)) of A and [N, round_up(N, 256)) of
                         //   W are readable memory (contents irrelevant): enables the load path
                         //   without per-lane row clamping
+  // bf16 path, RMSNorm folded into the GEMMs around it (see launch_fold_gamma):
+  //   producer (EPI_RESIDUAL): also store the updated residual rows as bf16 to xb and the sum
+  //   of their squares per 128-column segment to stats_out[m][n / 128]
+  void* xb;             // bf16 [M, ldxb] or nullptr
+  int ldxb;
+  float* stats_out;     // [M, stats_n] or nullptr (requires N % 128 == 0)
+  //   consumer (any epilogue): the accumulator of row m is multiplied by
+  //   rsqrt(sum_j stats_in[m][j] * stats_inv_dim + stats_eps) before bias / rotary / activation
+  const float* stats_in;  // [M, stats_n] or nullptr
+  int stats_n;
+  float stats_inv_dim, stats_eps;
   int tile_cfg;         // bf16 path: 0 = automatic choice, k > 0 = tile variant k - 1 (tuning)
   int group_m;          // bf16 path: row tiles per rasterisation group (set by the launcher)
   unsigned long long* trace;  // tuning builds only (EPD_GEMM_TRACE): per-wave stall cycle counters
@@ -101,6 +112,9 @@ bool launch_attn_bf16(const AttnArgs& a, hipStream_t s);  // false: head_dim not
 // query rows per work item for segments up to max_seg_len (0 = unsupported head_dim);
 // never smaller than attn_q_tile(bf16, head_dim, 1)
 int attn_q_tile(bool bf16, int head_dim, int max_seg_len);
+// W[n][k] *= gamma[k] (bf16, in place): folds the scale of an RMSNorm into the weights of the
+// linear layer that consumes its output, so that  (x * rstd * gamma) W^T = rstd * (x (W gamma)^T)
+void launch_fold_gamma(void* w, const void* gamma, int N, int K, hipStream_t s);
 // dst[(sec, h, 2p+e)] = src[(sec, h, p + e*pairs)] for the Q and K sections, V copied
 void launch_permute_qkv(const void* src_w, const void* src_b, void* dst_w, void* dst_b,
                         int hidden, int num_heads, int head_dim, int elem_bytes, hipStream_t s);

@@ -73,6 +73,18 @@ __device__ __forceinline__ float gelu_tanh_fast(float x) {
 
 enum OutKind : int { OUT_BF16 = 0, OUT_F32 = 1 };
 
+// Sum over aligned groups of G = 16 or 32 consecutive lanes; every lane of a group gets the sum.
+template <int G> __device__ __forceinline__ float group_sum(float x) {
+  static_assert(G == 16 || G == 32, "group size");
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // quad_perm 1,0,3,2
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // quad_perm 2,3,0,1
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));  // row_mirror
+  if constexpr (G == 32)
+    x += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((int)((threadIdx.x ^ 16) & 63) * 4, __builtin_bit_cast(int, x)));
+  return x;
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
@@ -201,6 +213,31 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(sw + (it * NT + wave * 64) * 16), 16, 0, 0);
     }
   };
+  // Folded RMSNorm (consumer side): scale of row m = rsqrt(mean of squares + eps), from the
+  // per-segment sums the producing GEMM left.  Computed first, so that the loads complete in
+  // the shadow of the main loop, and kept in LDS behind the stages and the staging area (the
+  // barriers of the main loop make it visible to the epilogue).
+  float* const row_scale = (float*)(lds + T::LDS_BYTES);
+  const bool scaled = g.stats_in != nullptr;
+  // eight segments (hidden 1024): the loads are issued here, ahead of the first operand
+  // loads, and only consumed after the first barrier
+  static_assert(BM <= NT, "one row scale per thread");
+  const bool scaled8 = scaled && g.stats_n == 8;
+  float4 st_a = make_float4(0.f, 0.f, 0.f, 0.f), st_b = st_a;
+  if (scaled8) {
+    if (tid < BM) {
+      const float4* sp = (const float4*)(g.stats_in + (size_t)min(m0 + tid, g.M - 1) * 8);
+      st_a = sp[0]; st_b = sp[1];
+    }
+  } else if (scaled) {
+    for (int r = tid; r < BM; r += NT) {
+      const float* sp = g.stats_in + (size_t)min(m0 + r, g.M - 1) * g.stats_n;
+      float ss = 0.f;
+      for (int j = 0; j < g.stats_n; ++j) ss += sp[j];
+      row_scale[r] = 1.0f / sqrtf(fmaf(ss, g.stats_inv_dim, g.stats_eps));
+    }
+  }
+
   const int nk = (g.K + BK - 1) / BK;
   const bool ragged_k = (g.K % BK) != 0;
   auto issue_step = [&](int stage, int kt) {      // kt < nk
@@ -273,6 +310,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   issue_step(0, 0);
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
+  if (scaled8 && tid < BM) {
+    const float ss = ((st_a.x + st_a.y) + (st_a.z + st_a.w)) + ((st_b.x + st_b.y) + (st_b.z + st_b.w));
+    row_scale[tid] = 1.0f / sqrtf(fmaf(ss, g.stats_inv_dim, g.stats_eps));
+  }
   if (nk > 1 && !(g.tile_cfg & 256)) issue_step(1, 1);
   read_frags(I0{}, I0{}, I0{});
 
@@ -372,14 +413,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       const bool full = m + 7 < g.M;
       if (full) { vc0 = *(const int4*)(g.vcol + m); vc1 = *(const int4*)(g.vcol + m + 4); }
       const bool fast = full && (vc1.w - vc0.x == 7) && ((vc0.x & 7) == 0);
+      float4 rs0 = make_float4(1.f, 1.f, 1.f, 1.f), rs1 = rs0;
+      if (scaled) { rs0 = *(const float4*)(row_scale + tl); rs1 = *(const float4*)(row_scale + tl + 4); }
       for (int r = tid / LPRV; r < HALF; r += RPS) {
         const int n = n0 + h * HALF + r;
         if (n >= g.N || m >= g.M) continue;
         const float bv = bias ? bf16_bits_to_float(bias[n]) : 0.f;
         const float4 e0 = *(const float4*)(lds + r * ROWE + tl * 4);
         const float4 e1 = *(const float4*)(lds + r * ROWE + tl * 4 + 16);
-        const uint2 p0 = pack_bf16x4(e0.x + bv, e0.y + bv, e0.z + bv, e0.w + bv);
-        const uint2 p1 = pack_bf16x4(e1.x + bv, e1.y + bv, e1.z + bv, e1.w + bv);
+        const uint2 p0 = pack_bf16x4(fmaf(e0.x, rs0.x, bv), fmaf(e0.y, rs0.y, bv), fmaf(e0.z, rs0.z, bv), fmaf(e0.w, rs0.w, bv));
+        const uint2 p1 = pack_bf16x4(fmaf(e1.x, rs1.x, bv), fmaf(e1.y, rs1.y, bv), fmaf(e1.z, rs1.z, bv), fmaf(e1.w, rs1.w, bv));
         uint16_t* vrow = vt + (size_t)(n - g.qk_cols) * g.vt_stride;
         if (fast) {
           *(uint4*)(vrow + vc0.x) = make_uint4(p0.x, p0.y, p1.x, p1.y);
@@ -395,6 +438,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     constexpr int LPR4 = HALF / 4, RPS = NT / LPR4;    // lanes per row (4 columns each), rows per sweep
     static_assert(BM % RPS == 0, "sweeps");
     const int cl = (tid % LPR4) * 4;                   // first of the lane's 4 columns inside the half
+    static_assert(HALF == 64 || HALF == 128, "sum-of-squares segments are 128 columns");
+    [[maybe_unused]] float seg_ss[BM / RPS];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       __syncthreads();
@@ -430,7 +475,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         const int m = m0 + r;
         if (m >= g.M) continue;
         const float4 e = *(const float4*)(lds + r * ROWE + cl * 4);
-        float v0 = e.x + b0, v1 = e.y + b1, v2 = e.z + b2, v3 = e.w + b3;
+        const float rs = scaled ? row_scale[r] : 1.0f;
+        float v0 = fmaf(e.x, rs, b0), v1 = fmaf(e.y, rs, b1), v2 = fmaf(e.z, rs, b2), v3 = fmaf(e.w, rs, b3);
         if constexpr (EPI == EPI_QKV) {
           if (g.rot) {
             const float4 cs = *(const float4*)(g.rot + (size_t)m * g.rot_pairs + pr);
@@ -448,6 +494,18 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
           float4 x = *xp;
           x.x += v0; x.y += v1; x.z += v2; x.w += v3;
           *xp = x;
+          // folded RMSNorm (producer side): the raw rows in bf16 for the next GEMM, and their
+          // sums of squares per 128-column segment (HALF = 64: two passes make one segment)
+          if (g.xb) *(uint2*)((uint16_t*)g.xb + (size_t)m * g.ldxb + n) = pack_bf16x4(x.x, x.y, x.z, x.w);
+          if (g.stats_out) {
+            const float ss = group_sum<LPR4>(fmaf(x.x, x.x, fmaf(x.y, x.y, fmaf(x.z, x.z, x.w * x.w))));
+            if constexpr (HALF == 128) {
+              if ((tid % LPR4) == 0) g.stats_out[(size_t)m * g.stats_n + (n0 + h * HALF) / 128] = ss;
+            } else {
+              seg_ss[sw] = (h == 0) ? ss : seg_ss[sw] + ss;
+              if (h == 1 && (tid % LPR4) == 0) g.stats_out[(size_t)m * g.stats_n + n0 / 128] = seg_ss[sw];
+            }
+          }
         } else if constexpr (OUT == OUT_F32) {
           *(float4*)((float*)g.out + (size_t)m * g.ldo + n) = make_float4(v0, v1, v2, v3);
         } else {
@@ -487,7 +545,7 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 
 template <class T, int EPI, int OUT, bool GATHER, bool FAST>
 __global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g) {
-  __shared__ __attribute__((aligned(1024))) char lds[T::LDS_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds[T::LDS_BYTES + T::BM * 4];   // + per-row scales of the epilogue
   const int tiles_n = (g.N + T::BN - 1) / T::BN, tiles_m = (g.M + T::BM - 1) / T::BM;
   int tm, tn;
   tile_coords(xcd_remap(blockIdx.x, gridDim.x), tiles_m, tiles_n, g.group_m, tm, tn);

@@ -212,4 +212,21 @@ void launch_permute_qkv(const void* src_w, const void* src_b, void* dst_w, void*
                        (const uint16_t*)src_b, (uint16_t*)dst_w, (uint16_t*)dst_b, hidden, head_dim);
 }
 
+// ---------------------------------------------------------------- gamma folding (create time)
+__global__ __launch_bounds__(256) void fold_gamma_kernel(uint16_t* __restrict__ w, const uint16_t* __restrict__ gamma,
+                                                         long total, int K) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int k = (int)(i % K);
+  const float v = __uint_as_float((uint32_t)w[i] << 16) * __uint_as_float((uint32_t)gamma[k] << 16);
+  __bf16 r = (__bf16)v;   // round to nearest even
+  w[i] = *(uint16_t*)&r;
+}
+
+void launch_fold_gamma(void* w, const void* gamma, int N, int K, hipStream_t s) {
+  const long total = (long)N * K;
+  hipLaunchKernelGGL(fold_gamma_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (uint16_t*)w,
+                     (const uint16_t*)gamma, total, K);
+}
+
 }  // namespace epd
