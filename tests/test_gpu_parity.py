@@ -88,6 +88,23 @@ def test_bf16_wide_activation_range(act):
     parity(small("bf16", num_layers=1, act=act), RAGGED, std=0.2)
 
 
+def test_bf16_rmsnorm_gains_far_from_one():
+    # hidden 256 is a multiple of 128, so the block norms are folded into the GEMMs (gain into
+    # the consuming weights, 1/rms onto the accumulator rows); gains spread over [1/4, 4] make a
+    # missing or misplaced gain a gross error, in the first block (norm kernel) and in later ones
+    cfg = small("bf16", num_layers=3)
+    gw, layers, patches, cu, grid = case(cfg, RAGGED)
+    rng = np.random.default_rng(5)
+    for lw in layers:
+        for name in ("norm1_g", "norm2_g"):
+            lw[name] = W.round_to_dtype(np.exp2(rng.uniform(-2.0, 2.0, size=lw[name].shape)).astype(np.float32), cfg.dtype)
+    log("case %s: RMSNorm gains in [0.25, 4], L=3" % cfg.name)
+    ref, ref_h = O.encode(cfg, gw, layers, patches, cu, grid, return_hidden=True)
+    got, got_h = run_gpu(cfg, gw, layers, patches, cu, grid, want_hidden=True)
+    check(cfg, got_h, ref_h, "hidden")
+    check(cfg, got, ref, "output")
+
+
 def test_bf16_many_tiles():
     # > 2 row tiles of every GEMM, attention segments with several query and key tiles
     parity(small("bf16", num_layers=3), [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8)])
