@@ -207,19 +207,34 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) { mrun[nq] = -INFINITY; lrun[nq] = 0.f; }
 
-  const float c = a.scale * 1.44269504088896340736f;   // scores are handled in log2 units
+  // Q arrives multiplied by 1/sqrt(d) * log2(e) (folded into the QKV projection before its
+  // bf16 rounding), so K Q^T already is the score in log2 units.
+  // CREF (one 32-row group per wave): the softmax reference is subtracted inside the matrix
+  // cores -- the first MFMA of a score tile starts from an accumulator preset to -reference --
+  // so that a probability is exp2 of the accumulator itself, without a multiply-add per score.
+  // The preset only changes when the reference moves (rare, see kLag).  It costs 16 registers
+  // per 32-row group: used where that does not lower the occupancy (d >= 72: +3-6 % measured;
+  // at d = 64 the kernel would drop from three to two waves per SIMD and lose 5 %).
+  constexpr bool CREF = NQ == 1 && DH >= 72;
+  f32x16 cref[NQ];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) cref[nq][v] = 0.f;
 
-  auto compute = [&](auto ST, int nvalid) {
+  auto compute = [&](auto ST, int nvalid, const bool first) {
     constexpr int st = decltype(ST)::value;
     constexpr int SO = st * STAGE;
     // ---- S^T = K Q^T: K fragments of k-step ks+1 are requested before step ks is multiplied
     f32x16 s[2][NQ];
+    if constexpr (!CREF) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq)
+        for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[kb][nq][v] = 0.f;
+          for (int v = 0; v < 16; ++v) s[kb][nq][v] = 0.f;
+    }
     bf16x8 kf[2][2];
     lds_read16<SO>(kf[0][0], k_rd[0]);
     lds_read16<SO + 32 * ROWK>(kf[0][1], k_rd[0]);
@@ -237,8 +252,10 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
-          s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[cur][kb], qf[nq][ks].v, s[kb][nq], 0, 0, 0);
+        for (int nq = 0; nq < NQ; ++nq) {
+          if (CREF && ks == 0) s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[cur][kb], qf[nq][ks].v, cref[nq], 0, 0, 0);
+          else s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[cur][kb], qf[nq][ks].v, s[kb][nq], 0, 0, 0);
+        }
     }
     if (nvalid < BKV) {
 #pragma unroll
@@ -254,8 +271,11 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     }
 
     // ---- online softmax, per query column (= per lane pair l, l ^ 32)
+    // The reference only follows the true maximum when it falls behind by more than kLag (log2
+    // units): in between, probabilities may reach 2^kLag instead of 1, which fp32 sums and bf16
+    // operands hold without loss, and nothing needs rescaling.
     Frag8 pb[NQ][2][2];
-    float alpha[NQ];
+    float alpha[NQ], delta[NQ];
     bool moved = false;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
@@ -264,37 +284,59 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][nq][v]);
-      mx = half_swap_max(mx) * c;
-      // the reference maximum only follows the true one when it falls behind by more than
-      // kLag (log2 units): in between, probabilities may reach 2^kLag instead of 1, which
-      // fp32 sums and bf16 operands hold without loss, and no rescale is needed
-      const bool lag = mx > mrun[nq] + kLag;
-      const float mnew = lag ? mx : mrun[nq];
-      alpha[nq] = __builtin_amdgcn_exp2f(mrun[nq] - mnew);
-      moved = moved || lag;
-      mrun[nq] = mnew;
-      float psum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int mm = 0; mm < 2; ++mm)
-#pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][8 * mm + e], c, -mnew));
-            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][8 * mm + e + 1], c, -mnew));
-            if constexpr (!SUMROW) psum += p0 + p1;
-            pb[nq][kb][mm].w[e >> 1] = pack2(p0, p1);
-          }
-      if constexpr (!SUMROW) lrun[nq] = lrun[nq] * alpha[nq] + psum;
+      mx = half_swap_max(mx);
+      if constexpr (CREF) {
+        // mx = true maximum - reference (the very first tile is measured against reference 0)
+        const bool lag = first || mx > kLag;
+        delta[nq] = lag ? mx : 0.f;
+        alpha[nq] = first ? 0.f : __builtin_amdgcn_exp2f(-delta[nq]);
+        moved = moved || lag;
+        mrun[nq] = (first ? 0.f : mrun[nq]) + delta[nq];
+      } else {
+        const bool lag = mx > mrun[nq] + kLag;
+        const float mnew = lag ? mx : mrun[nq];
+        alpha[nq] = __builtin_amdgcn_exp2f(mrun[nq] - mnew);
+        moved = moved || lag;
+        mrun[nq] = mnew;
+        delta[nq] = mnew;      // subtracted from every score below
+      }
     }
-    // rescale the output accumulators only if some row's maximum moved (wave-uniform test)
-    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+    const bool any_moved = __builtin_amdgcn_ballot_w64(moved) != 0;
+    auto probs = [&](auto SUBT) {
+      constexpr bool sub = decltype(SUBT)::value;
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq)
+      for (int nq = 0; nq < NQ; ++nq) {
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+              const float x0 = s[kb][nq][8 * mm + e], x1 = s[kb][nq][8 * mm + e + 1];
+              const float p0 = __builtin_amdgcn_exp2f(sub ? x0 - delta[nq] : x0);
+              const float p1 = __builtin_amdgcn_exp2f(sub ? x1 - delta[nq] : x1);
+              if constexpr (!SUMROW) psum += p0 + p1;
+              pb[nq][kb][mm].w[e >> 1] = pack2(p0, p1);
+            }
+        if constexpr (!SUMROW) lrun[nq] = lrun[nq] * alpha[nq] + psum;
+      }
+    };
+    if (!CREF || any_moved) probs(std::true_type{}); else probs(std::false_type{});
+    // rescale the output accumulators (and renew the accumulator preset) only if some row's
+    // reference moved (wave-uniform test)
+    if (any_moved) {
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) {
 #pragma unroll
         for (int db = 0; db < DBX; ++db)
 #pragma unroll
           for (int v = 0; v < 16; ++v) o[db][nq][v] *= alpha[nq];
+        if constexpr (CREF) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) cref[nq][v] = -mrun[nq];
+        }
+      }
     }
 
     // ---- O^T += V^T P^T: fragments of one 32-channel block are requested ahead of its MFMAs
@@ -334,12 +376,12 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     if (j + 1 < ntiles) issue(1, j + 1);
-    if (wave_active) compute(std::integral_constant<int, 0>{}, w.seg_len - j * BKV);
+    if (wave_active) compute(std::integral_constant<int, 0>{}, w.seg_len - j * BKV, j == 0);
     if (j + 1 < ntiles) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
       if (j + 2 < ntiles) issue(0, j + 2);
-      if (wave_active) compute(std::integral_constant<int, 1>{}, w.seg_len - (j + 1) * BKV);
+      if (wave_active) compute(std::integral_constant<int, 1>{}, w.seg_len - (j + 1) * BKV, false);
     }
   }
 

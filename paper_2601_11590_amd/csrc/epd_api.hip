@@ -499,6 +499,7 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
       g.M = T; g.N = 3 * D; g.K = D; g.epilogue = EPI_QKV; g.out = QKV; g.ldo = bf ? 2 * D : 3 * D;
       g.rot = rot; g.rot_pairs = L.pairs; g.head_dim = c.head_dim; g.qk_cols = 2 * D;
       g.vt = Vt; g.vt_stride = L.vt_stride; g.vcol = vcol;
+      if (bf) { g.q_cols = D; g.q_scale = (float)(1.4426950408889634 / std::sqrt((double)c.head_dim)); }
       gemm(EPD_STEP_QKV, g);
     }
     {  // block-diagonal non-causal attention

@@ -40,6 +40,8 @@ struct GemmArgs {
   int rot_pairs;        // head_dim / 2
   int head_dim;
   int qk_cols;          // 2 * hidden
+  float q_scale;        // bf16 path: columns < q_cols (the Q third) are multiplied by this after the
+  int q_cols;           //   rotation, before rounding (0 = no scaling)
   void* vt;             // bf16 [hidden, vt_stride] transposed V
   int vt_stride;
   const int32_t* vcol;  // [M] column of token m in vt
@@ -78,7 +80,8 @@ struct AttnArgs {
   const AttnWork* work;
   int num_work;
   int num_heads, head_dim;
-  float scale;          // 1 / sqrt(head_dim)
+  float scale;          // 1 / sqrt(head_dim); fp32 path only -- the bf16 path expects Q already
+                        //   multiplied by scale * log2(e) (GemmArgs::q_scale)
   int q_tile;           // query rows per work item (attn_q_tile of this call)
 };
 

@@ -484,6 +484,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
             const float r2 = v2 * cs.z - v3 * cs.w, r3 = v2 * cs.w + v3 * cs.z;
             v0 = r0; v1 = r1; v2 = r2; v3 = r3;
           }
+          // the softmax scale (in log2 units) rides on Q: one rounding of q * scale instead of
+          // a multiply per score in the attention kernel
+          if (n < g.q_cols) { v0 *= g.q_scale; v1 *= g.q_scale; v2 *= g.q_scale; v3 *= g.q_scale; }
         }
         if constexpr (EPI == EPI_GELU) {
           if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
