@@ -42,6 +42,7 @@ struct LayerW {   // byte offsets into the workspace; SIZE_MAX = absent
 struct Layout {
   int es;            // element size of cfg.dtype
   int pdim, pairs, mm, max_tm, max_work, vt_stride;
+  int fpad;          // leading dimension of Hd and of the fc2 weights: mlp_dim, padded to 64 on the bf16 path
   size_t patch_w, patch_b, final_g, final_b, merge_w, merge_b;
   std::vector<LayerW> layers;
   size_t x, xn, qkv, vt, o, hd, rot, merge_idx, vcol, pair_freq, pair_axis, zeros, meta, stats;
@@ -65,6 +66,9 @@ Layout make_layout(const epd_encode_cfg& c) {
   L.mm = c.merge * c.merge;
   L.max_tm = c.max_tokens / L.mm;
   L.max_work = c.max_tokens / q_tile(c, 1) + c.max_segments + 1;   // smallest tile the kernels use
+  // bf16: the K dimension of the fc2 GEMM is padded with zeros to a multiple of the K step, so
+  // that it takes the GEMM's fast load path for any mlp_dim (4304 -> 4352)
+  L.fpad = bf ? (int)align_up((size_t)c.mlp_dim, 64) : c.mlp_dim;
   L.vt_stride = (int)align_up((size_t)c.max_tokens + (size_t)c.max_segments * kVtAlign, kVtAlign);
   const bool ln = c.norm == EPD_LAYERNORM, bias = c.use_bias != 0;
   size_t off = 0;
@@ -92,7 +96,7 @@ Layout make_layout(const epd_encode_cfg& c) {
     w.norm2_b = take(D * es, ln);
     w.fc1_w = take(F * D * es);
     w.fc1_b = take(F * es, bias);
-    w.fc2_w = take(D * F * es);
+    w.fc2_w = take(D * (size_t)L.fpad * es);
     w.fc2_b = take(D * es, bias);
   }
   L.x = take(T * D * 4);
@@ -100,7 +104,7 @@ Layout make_layout(const epd_encode_cfg& c) {
   L.qkv = take(T * (bf ? 2 : 3) * D * es);
   L.vt = take(D * (size_t)L.vt_stride * 2, bf);
   L.o = take(T * D * es);
-  L.hd = take(T * F * es);
+  L.hd = take(T * (size_t)L.fpad * es);
   L.rot = take(T * (size_t)std::max(L.pairs, 1) * sizeof(float2));
   L.merge_idx = take((size_t)std::max(L.max_tm, 1) * L.mm * 4);
   L.vcol = take(T * 4, bf);
@@ -318,7 +322,16 @@ epd_status epd_encode_create(const epd_encode_cfg* cfg, epd_handle* out) {
     EPD_CW(d.norm2_b, s.norm2_b, D * es);
     EPD_CW(d.fc1_w, s.fc1_w, F * D * es);
     EPD_CW(d.fc1_b, s.fc1_b, F * es);
-    EPD_CW(d.fc2_w, s.fc2_w, D * F * es);
+    if (L.fpad == (int)F) {
+      EPD_CW(d.fc2_w, s.fc2_w, D * F * es);
+    } else {   // rows of mlp_dim elements into rows of fpad, the pad cleared
+      if (!s.fc2_w) return fail(EPD_ERR_INVALID_ARG);
+      if (hipMemsetAsync(h->ws + d.fc2_w, 0, D * (size_t)L.fpad * es, 0) != hipSuccess ||
+          hipMemcpy2DAsync(h->ws + d.fc2_w, (size_t)L.fpad * es, s.fc2_w, F * es, F * es, D, hipMemcpyDeviceToDevice, 0) != hipSuccess) {
+        h->err = "copying the fc2 weights failed";
+        return fail(EPD_ERR_HIP);
+      }
+    }
     EPD_CW(d.fc2_b, s.fc2_b, D * es);
     if (L.fold_rms) {
       // norm2 -> fc1 in every block; norm1 -> qkv from the second block on (the first block's
@@ -341,6 +354,10 @@ epd_status epd_encode_create(const epd_encode_cfg* cfg, epd_handle* out) {
     hipError_t e = hipMemcpy(h->ws + L.pair_freq, freq.data(), L.pairs * 8, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(h->ws + L.pair_axis, axis.data(), L.pairs * 4, hipMemcpyHostToDevice);
     if (e != hipSuccess) { h->err = fmt("rotary table upload failed: %s", hipGetErrorString(e)); return fail(EPD_ERR_HIP); }
+  }
+  if (L.fpad != cfg->mlp_dim) {   // pad columns of Hd stay zero: the fc1 GEMM never writes them
+    hipError_t e0 = hipMemsetAsync(h->ws + L.hd, 0, (size_t)cfg->max_tokens * L.fpad * es, 0);
+    if (e0 != hipSuccess) { h->err = fmt("hipMemsetAsync failed: %s", hipGetErrorString(e0)); return fail(EPD_ERR_HIP); }
   }
   hipError_t e = hipMemsetAsync(h->ws + L.zeros, 0, 256, 0);
   if (e != hipSuccess) { h->err = fmt("hipMemsetAsync failed: %s", hipGetErrorString(e)); return fail(EPD_ERR_HIP); }
@@ -463,8 +480,8 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
     launch_plan(p, st);
   }
 
-  auto gemm = [&](int step, GemmArgs& g) {
-    StepTimer tm(h, step, 2.0 * g.M * (double)g.N * g.K, st);
+  auto gemm = [&](int step, GemmArgs& g, int k_counted = 0) {   // k_counted: K without padding
+    StepTimer tm(h, step, 2.0 * g.M * (double)g.N * (k_counted ? k_counted : g.K), st);
     g.zeros = h->ws + L.zeros;
     // operands that live in the workspace may be read past their last row (see make_layout)
     g.overread_ok = (g.A != packed_patches && !g.gather) ? 1 : 0;
@@ -525,15 +542,16 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
       GemmArgs g{};
       if (L.fold_rms) consume_stats(g);
       g.A = Xn; g.lda = D; g.W = h->at<void>(w.fc1_w); g.bias = h->at<void>(w.fc1_b);
-      g.M = T; g.N = F; g.K = D; g.epilogue = EPI_GELU; g.act = c.act; g.out = Hd; g.ldo = F;
+      g.M = T; g.N = F; g.K = D; g.epilogue = EPI_GELU; g.act = c.act; g.out = Hd; g.ldo = L.fpad;
       gemm(EPD_STEP_FC1, g);
     }
     {  // X += Hd W2^T + b2
       GemmArgs g{};
-      g.A = Hd; g.lda = F; g.W = h->at<void>(w.fc2_w); g.bias = h->at<void>(w.fc2_b);
-      g.M = T; g.N = D; g.K = F; g.epilogue = EPI_RESIDUAL; g.resid = X; g.ldr = D;
+      g.A = Hd; g.lda = L.fpad; g.W = h->at<void>(w.fc2_w); g.ldw = L.fpad; g.bias = h->at<void>(w.fc2_b);
+      g.M = T; g.N = D; g.K = L.fpad;   // pad columns of Hd and of the weights are zero
+      g.epilogue = EPI_RESIDUAL; g.resid = X; g.ldr = D;
       if (L.fold_rms && l + 1 < c.num_layers) produce_stats(g);
-      gemm(EPD_STEP_FC2, g);
+      gemm(EPD_STEP_FC2, g, (int)F);
     }
   }
   const void* Z = X;   // fp32 path without a final norm reads the residual stream directly
