@@ -105,6 +105,34 @@ def test_bf16_rmsnorm_gains_far_from_one():
     check(cfg, got, ref, "output")
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_bf16_seeded_random_small_configurations(seed):
+    # shapes that are not tidy multiples of the kernels' tiles: odd head counts, MLP widths off the
+    # 64-wide K step, every head dim, both norms, all rotary kinds, merge 1 and 2, ragged grids
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([32, 64, 72, 80, 96, 128]))
+    heads = int(rng.integers(1, 5))
+    hidden = d * heads
+    rope = str(rng.choice(["none", "2d", "3d"]))
+    half = d // 2
+    if rope == "none":
+        pairs = (0, 0, 0)
+    elif rope == "2d":
+        a = int(rng.integers(1, half)); pairs = (0, a, half - a)
+    else:
+        a = int(rng.integers(1, half - 1)); b = int(rng.integers(1, half - a)); pairs = (a, b, half - a - b)
+    merge = int(rng.choice([1, 2]))
+    patch, tpatch = [(4, 1), (4, 2), (2, 2)][int(rng.integers(0, 3))]    # patch length a multiple of 8
+    cfg = small("bf16", name="rand%d" % seed, num_layers=int(rng.integers(1, 4)), hidden=hidden, num_heads=heads,
+                head_dim=d, mlp_dim=int(rng.integers(8, 80)) * 8, patch=patch,
+                temporal_patch=tpatch, norm=str(rng.choice(["rmsnorm", "layernorm"])),
+                act=str(rng.choice(["gelu_erf", "gelu_tanh"])), use_bias=bool(rng.integers(0, 2)),
+                rope=rope, rope_pairs=pairs, out_dim=int(rng.integers(4, 40)) * 8, merge=merge, seed=100 + seed)
+    grids = [(int(rng.integers(1, 4)), merge * int(rng.integers(1, 9)), merge * int(rng.integers(1, 9)))
+             for _ in range(int(rng.integers(1, 6)))]
+    parity(cfg, grids, segments=str(rng.choice(["item", "frame"])))
+
+
 def test_bf16_many_tiles():
     # > 2 row tiles of every GEMM, attention segments with several query and key tiles
     parity(small("bf16", num_layers=3), [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8)])
