@@ -146,3 +146,34 @@ def test_product_path_never_touches_the_oracle():
                 assert "oracle" not in text.replace("CPU oracle", "").replace("the oracle's callers", ""), f
     code = "import sys; import paper_2601_11590_amd.binding; assert not any(m.startswith('oracle') for m in sys.modules)"
     subprocess.run([sys.executable, "-c", code], check=True, cwd=ROOT)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message (this build runs on exactly one GPU); it must
+    do so before touching the GPU, so the check runs anywhere."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_workspace_pads_mlp_width_and_keeps_a_read_tail():
+    """bf16 workspaces grow with a padded MLP width (4304 -> 4352 columns of hidden activations and
+    fc2 weights) and hold a tail behind the last buffer; fp32 ones do neither."""
+    base = dict(name="w", num_layers=1, hidden=128, num_heads=2, head_dim=64, patch=4, temporal_patch=1,
+                norm="layernorm", rope="2d", rope_pairs=(0, 16, 16), out_dim=64, seed=1)
+    sizes = {}
+    for dtype in ("bf16", "f32"):
+        for mlp in (128, 136):
+            cfg = W.EncoderConfig(dtype=dtype, mlp_dim=mlp, **base)
+            sizes[dtype, mlp] = B.epd_encode_workspace_bytes(B.make_cfg(cfg, 256, 4, 4))
+            assert sizes[dtype, mlp] > 0
+    es = 2
+    # 136 pads to 192 columns: (192 - 128) more columns of Hd (256 tokens) and of fc2_w (128 rows),
+    # fc1 rows grow by 8 without padding; everything is rounded up to 256-byte blocks
+    grow_bf16 = sizes["bf16", 136] - sizes["bf16", 128]
+    assert grow_bf16 >= (256 + 128) * 64 * es
+    grow_f32 = sizes["f32", 136] - sizes["f32", 128]
+    assert 0 < grow_f32 <= (256 + 128 + 128 + 1) * 8 * 4 + 4 * 256
