@@ -433,6 +433,67 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         }
       }
     }
+  } else if constexpr ((EPI == EPI_STORE || EPI == EPI_GELU) && OUT == OUT_BF16) {
+    // bf16 output with a per-element epilogue: scale, bias and activation are applied in the
+    // MFMA layout (a lane holds 4 consecutive columns of one token), the results are staged as
+    // bf16 -- the whole tile in one pass, half the LDS traffic of the fp32 staging below -- and
+    // leave as 16-byte row-contiguous stores.
+    constexpr int ROWO = BN * 2 + 16;                  // padded: 16 consecutive rows hit 16 different bank groups
+    static_assert(BM * ROWO <= T::LDS_BYTES, "bf16 staging area");
+    float rsv[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) rsv[i] = 1.0f;
+    __syncthreads();
+    if (scaled) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) rsv[i] = row_scale[wm * WM + i * 32 + l32];
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = wn * WN + j * 32 + q * 8 + lg * 4;
+        float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+        if (bias && n0 + nl < g.N) {                   // N is a multiple of 4: all or nothing
+          const uint2 bb = *(const uint2*)(bias + n0 + nl);
+          b0 = bf16_bits_to_float(bb.x & 0xffff); b1 = bf16_bits_to_float(bb.x >> 16);
+          b2 = bf16_bits_to_float(bb.y & 0xffff); b3 = bf16_bits_to_float(bb.y >> 16);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int ml = wm * WM + i * 32 + l32;
+          float v0 = fmaf(acc[i][j][4 * q], rsv[i], b0), v1 = fmaf(acc[i][j][4 * q + 1], rsv[i], b1);
+          float v2 = fmaf(acc[i][j][4 * q + 2], rsv[i], b2), v3 = fmaf(acc[i][j][4 * q + 3], rsv[i], b3);
+          if constexpr (EPI == EPI_GELU) {
+            if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
+            else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
+          }
+          *(uint2*)(lds + ml * ROWO + nl * 2) = pack_bf16x4(v0, v1, v2, v3);
+        }
+      }
+    __syncthreads();
+    constexpr int CPRO = BN / 8, RPSO = NT / CPRO;     // 16-byte chunks per row, rows per sweep
+    static_assert(BM % RPSO == 0, "sweeps");
+    const int c8 = (tid % CPRO) * 8;
+    const int n = n0 + c8;
+    uint16_t* const outp = (uint16_t*)g.out;
+    const bool vec = (g.ldo % 8 == 0) && (((size_t)outp & 15) == 0) && n + 8 <= g.N;
+    if (n < g.N) {
+#pragma unroll
+      for (int sw = 0; sw < BM / RPSO; ++sw) {
+        const int r = sw * RPSO + tid / CPRO;
+        const int m = m0 + r;
+        if (m >= g.M) continue;
+        const uint4 v = *(const uint4*)(lds + r * ROWO + c8 * 2);
+        uint16_t* dst = outp + (size_t)m * g.ldo + n;
+        if (vec) {
+          *(uint4*)dst = v;
+        } else {
+          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+          for (int t = 0; t < 8 && n + t < g.N; ++t) dst[t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
+        }
+      }
+    }
   } else {
     constexpr int ROWE = HALF * 4 + 16;
     constexpr int LPR4 = HALF / 4, RPS = NT / LPR4;    // lanes per row (4 columns each), rows per sweep
