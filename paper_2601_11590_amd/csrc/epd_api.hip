@@ -121,10 +121,10 @@ Layout make_layout(const epd_encode_cfg& c) {
   L.fold_rms = bf && c.norm == EPD_RMSNORM && c.hidden % 128 == 0 && c.num_layers > 0;
   L.stats_n = c.hidden / 128;
   L.stats = take(T * (size_t)std::max(L.stats_n, 1) * 4, L.fold_rms);
-  // The bf16 GEMMs fetch whole 256-row operand tiles without clamping rows at the edge of a
+  // The bf16 GEMMs fetch whole operand tiles (up to 320 rows) without clamping rows at the edge of a
   // matrix (what lies beyond only feeds accumulators that are never stored); this tail keeps
   // such reads, from whichever buffer they start, inside the workspace.
-  if (bf) take(256 * std::max(std::max(D, F), (size_t)L.mm * D) * es);
+  if (bf) take(320 * std::max(std::max(D, (size_t)L.fpad), (size_t)L.mm * D) * es);
   L.total = off;
   return L;
 }

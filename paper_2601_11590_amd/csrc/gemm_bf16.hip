@@ -118,7 +118,9 @@ struct Tile {
   static constexpr int CPR = BK / 8;                     // 16-byte chunks per tile row
   static constexpr int LA = BM * CPR / NT, LW = BN * CPR / NT;   // load instructions per thread and stage
   static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
-  static constexpr int EPI_BYTES_A = BM * (BN / 2 * 4 + 16), EPI_BYTES_V = (BN / 2) * (BM * 4 + 16);
+  // fp32 epilogue staging: the tile's columns in 2 passes, or 4 where two would not fit LDS
+  static constexpr int EPI_PASSES = BM * (BN / 2 * 4 + 16) <= 136 * 1024 ? 2 : 4;
+  static constexpr int EPI_BYTES_A = BM * (BN / EPI_PASSES * 4 + 16), EPI_BYTES_V = (BN / EPI_PASSES) * (BM * 4 + 16);
   static constexpr int LDS_BYTES = (2 * STAGE_BYTES > EPI_BYTES_A ? 2 * STAGE_BYTES : EPI_BYTES_A) > EPI_BYTES_V
                                        ? (2 * STAGE_BYTES > EPI_BYTES_A ? 2 * STAGE_BYTES : EPI_BYTES_A) : EPI_BYTES_V;
   static_assert(BK == 32 || BK == 64, "BK");
@@ -378,9 +380,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   // one half of the tile's columns as fp32 (BM rows x BN/2 floats, rows padded by 16 bytes);
   // then every group of 32 lanes owns one row and a lane owns 4 consecutive columns, which is
   // where bias, activation, rotary and the residual add are applied.
-  constexpr int HALF = BN / 2;
-  constexpr int WPH = T::WAVES_N / 2;                 // wave columns per half
-  static_assert(T::WAVES_N % 2 == 0 && HALF % 32 == 0, "epilogue halves");
+  constexpr int NPASS = T::EPI_PASSES;
+  constexpr int HALF = BN / NPASS;                    // columns per pass
+  constexpr int WPH = T::WAVES_N / NPASS;             // wave columns per pass
+  static_assert(T::WAVES_N % NPASS == 0 && HALF % 32 == 0, "epilogue passes");
   const uint16_t* bias = (const uint16_t*)g.bias;
   wait_vmcnt<0>();
   if constexpr (VMODE) {
@@ -388,7 +391,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     constexpr int ROWE = BM * 4 + 16;
     uint16_t* vt = (uint16_t*)g.vt;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < NPASS; ++h) {
       __syncthreads();
       if (wn / WPH == h) {
 #pragma unroll
@@ -406,9 +409,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       }
       __syncthreads();
       // BM tokens per channel row: BM/8 lanes per row, 8 tokens (one 16-byte bf16 store) per lane
-      constexpr int LPRV = BM / 8, RPS = NT / LPRV;
+      constexpr int LPRV = BM / 8, RPS = NT / LPRV;      // threads beyond RPS whole rows idle
       const int tl = (tid % LPRV) * 8;
-      const int m = m0 + tl;
+      const int m = tid < RPS * LPRV ? m0 + tl : g.M;
       int4 vc0 = make_int4(0, 0, 0, 0), vc1 = make_int4(0, 0, 0, 0);
       const bool full = m + 7 < g.M;
       if (full) { vc0 = *(const int4*)(g.vcol + m); vc1 = *(const int4*)(g.vcol + m + 4); }
@@ -433,7 +436,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         }
       }
     }
-  } else if constexpr ((EPI == EPI_STORE || EPI == EPI_GELU) && OUT == OUT_BF16) {
+  } else if constexpr ((EPI == EPI_STORE || EPI == EPI_GELU) && OUT == OUT_BF16 && BM * (BN * 2 + 16) <= T::LDS_BYTES) {
     // bf16 output with a per-element epilogue: scale, bias and activation are applied in the
     // MFMA layout (a lane holds 4 consecutive columns of one token), the results are staged as
     // bf16 -- the whole tile in one pass, half the LDS traffic of the fp32 staging below -- and
@@ -502,7 +505,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     static_assert(HALF == 64 || HALF == 128, "sum-of-squares segments are 128 columns");
     [[maybe_unused]] float seg_ss[BM / RPS];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < NPASS; ++h) {
       __syncthreads();
       if (wn / WPH == h) {
 #pragma unroll
@@ -566,8 +569,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
             if constexpr (HALF == 128) {
               if ((tid % LPR4) == 0) g.stats_out[(size_t)m * g.stats_n + (n0 + h * HALF) / 128] = ss;
             } else {
-              seg_ss[sw] = (h == 0) ? ss : seg_ss[sw] + ss;
-              if (h == 1 && (tid % LPR4) == 0) g.stats_out[(size_t)m * g.stats_n + n0 / 128] = seg_ss[sw];
+              seg_ss[sw] = (h % 2 == 0) ? ss : seg_ss[sw] + ss;
+              if (h % 2 == 1 && (tid % LPR4) == 0) g.stats_out[(size_t)m * g.stats_n + (n0 + (h / 2) * 128) / 128] = seg_ss[sw];
             }
           }
         } else if constexpr (OUT == OUT_F32) {
@@ -646,13 +649,13 @@ static void launch_cfg(const GemmArgs& g, hipStream_t s) {
 using T0 = Tile<256, 256, 64, 2, 4, 1>;   // 8 waves, 128x64 wave tiles, 128 KB LDS, one block per CU
 using T2 = Tile<256, 128, 64, 2, 2, 1>;   // 4 waves, 128x64 wave tiles, 96 KB LDS
 using T4 = Tile<128, 128, 64, 2, 2, 2>;   // 4 waves, 64x64 wave tiles, 64 KB LDS, two blocks per CU
+using T5 = Tile<320, 256, 64, 2, 4, 1>;   // 8 waves, 160x64 wave tiles, 144 KB LDS
 
+// Tuning and test knob: EPD_GEMM_TILE = 0, 2, 4 or 5 forces that tile variant for every bf16
+// GEMM launched afterwards (read at every launch, so one process can try several).
 static int forced_tile() {
-  static int t = [] {
-    const char* e = getenv("EPD_GEMM_TILE");
-    return e ? atoi(e) : -1;
-  }();
-  return t;
+  const char* e = getenv("EPD_GEMM_TILE");
+  return e ? atoi(e) : -1;
 }
 
 static int num_cus() {
@@ -665,26 +668,35 @@ static int num_cus() {
   return n;
 }
 
-// Tile choice.  The 256 x 256 tile halves the operand traffic per flop and is the faster
+// Tile choice.  The 256 x 256 tile halves the operand traffic per flop and is the fastest
 // main loop, but runs one block per compute unit; the 128 x 128 tile runs two, which hides
 // the epilogue of one block behind the main loop of the other and quantises better on small
-// grids.  Both are priced by the fraction of block slots their last round of tiles leaves
-// idle, and the large tile is taken unless it loses clearly on that count.
+// grids; the 320 x 256 tile exists for the grids on which it needs one round of blocks less
+// than the others (a 6272 x 3072 output is 240 of its tiles, one round on 256 compute units).
+// Each is priced by the output area its busiest compute unit works through -- rounds of
+// blocks x blocks per unit x tile area -- over a measured relative rate, and the 256 x 256
+// tile is kept unless another is clearly (5 %) cheaper.
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
   int t = (g.tile_cfg & 255) > 0 ? (g.tile_cfg & 255) - 1 : forced_tile();
-  if (t != 0 && t != 2 && t != 4) {
-    const long n0 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-    const long n4 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128);
-    const long s0 = num_cus(), s4 = 2L * num_cus();
-    const double eff0 = (double)n0 / (double)((n0 + s0 - 1) / s0 * s0);
-    const double eff4 = (double)n4 / (double)((n4 + s4 - 1) / s4 * s4);
-    t = (n0 >= 4 * s0 || eff0 >= 0.95 * eff4) ? 0 : 4;
+  if (t != 0 && t != 2 && t != 4 && t != 5) {
+    const long cus = num_cus();
+    auto cost = [&](int bm, int bn, int blocks, double rate) {
+      const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
+      const long slots = cus * blocks;
+      return (double)((tiles + slots - 1) / slots) * blocks * bm * bn / rate;
+    };
+    const double c0 = cost(256, 256, 1, 1.0), c4 = cost(128, 128, 2, 0.85), c5 = cost(320, 256, 1, 0.9);
+    t = 0;
+    double best = c0 * 0.95;
+    if (c4 < best) { t = 4; best = c4; }
+    if (c5 < best) { t = 5; best = c5; }
   }
-  if (EPI == EPI_QKV && t == 0 && g.qk_cols % 256 != 0) t = 2;
+  if (EPI == EPI_QKV && (t == 0 || t == 5) && g.qk_cols % 256 != 0) t = 2;
   switch (t) {
     case 0: launch_cfg<T0, EPI, OUT, GATHER>(g, s); break;
     case 2: launch_cfg<T2, EPI, OUT, GATHER>(g, s); break;
+    case 5: launch_cfg<T5, EPI, OUT, GATHER>(g, s); break;
     default: launch_cfg<T4, EPI, OUT, GATHER>(g, s); break;
   }
 }

@@ -138,6 +138,16 @@ def test_bf16_many_tiles():
     parity(small("bf16", num_layers=3), [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8)])
 
 
+@pytest.mark.parametrize("tile", [0, 2, 4, 5])
+def test_bf16_every_gemm_tile_variant(tile, monkeypatch):
+    # each tile shape of the bf16 GEMM forced in turn (the library reads EPD_GEMM_TILE at every
+    # launch): 1304 tokens = several row tiles of each with a ragged last one; hidden 512 so
+    # that the 256-wide tiles keep whole Q|K column tiles
+    monkeypatch.setenv("EPD_GEMM_TILE", str(tile))
+    cfg = small("bf16", hidden=512, num_heads=8, mlp_dim=1088, out_dim=328)
+    parity(cfg, [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8), (1, 4, 16)])
+
+
 def test_c2_width_two_layers_full_batch():
     cfg = W.C2.replace(num_layers=2)
     parity(cfg, W.grids_for(W.C2))
