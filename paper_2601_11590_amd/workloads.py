@@ -182,6 +182,28 @@ def item_pixels(cfg: EncoderConfig, item: int, grid: Tuple[int, int, int], seed=
                       dtype=np.float32)
 
 
+def item_pixels_u8(cfg: EncoderConfig, item: int, grid: Tuple[int, int, int], src_hw: Tuple[int, int] = None,
+                   seed=None) -> np.ndarray:
+    """Raw pixels of one image or clip as a camera or decoder hands them over: uint8
+    [C, t*tp, Hs, Ws], a smooth seeded pattern (low-frequency waves per channel and frame) plus
+    uniform noise, so that neighbouring pixels are correlated as in natural images while every
+    byte value occurs.  src_hw defaults to the item's grid size in pixels (no resize needed)."""
+    t, h, w = grid
+    hs, ws = (h * cfg.patch, w * cfg.patch) if src_hw is None else src_hw
+    rng = np.random.default_rng([cfg.seed if seed is None else seed, _STREAM_PIXELS, item, 1])
+    frames = t * cfg.temporal_patch
+    yy = np.arange(hs, dtype=np.float32)[:, None] / max(hs, 1)
+    xx = np.arange(ws, dtype=np.float32)[None, :] / max(ws, 1)
+    out = np.empty((cfg.in_channels, frames, hs, ws), dtype=np.uint8)
+    for c in range(cfg.in_channels):
+        for f in range(frames):
+            fy, fx, ph = rng.uniform(0.5, 6.0), rng.uniform(0.5, 6.0), rng.uniform(0, 6.28)
+            wave = 0.5 + 0.35 * np.sin(6.2832 * (fy * yy + fx * xx) + ph)
+            noise = rng.random((hs, ws), dtype=np.float32) * 0.3 - 0.15
+            out[c, f] = np.clip(np.rint((wave + noise) * 255.0), 0, 255).astype(np.uint8)
+    return out
+
+
 def packed_patches(cfg: EncoderConfig, grids: Sequence[Tuple[int, int, int]], seed=None) -> np.ndarray:
     """All items' patch rows packed in item order, rounded to cfg.dtype, float32 [T, Pdim]."""
     rows = [patchify(item_pixels(cfg, i, g, seed), cfg.patch, cfg.temporal_patch)

@@ -76,3 +76,15 @@ def test_pixels_uniform_unit_interval():
     assert abs(px.mean() - 0.5) < 0.01
     p = W.packed_patches(W.C1, [(1, 16, 16)])
     assert p.shape == (256, 588)
+
+
+def test_raw_uint8_pixels_are_seeded_sized_and_use_the_whole_byte_range():
+    a = W.item_pixels_u8(W.C5, 2, (2, 4, 6))
+    assert a.dtype == np.uint8 and a.shape == (3, 4, 56, 84)            # frames = t * temporal_patch, grid size in pixels
+    assert np.array_equal(a, W.item_pixels_u8(W.C5, 2, (2, 4, 6)))
+    assert not np.array_equal(a, W.item_pixels_u8(W.C5, 3, (2, 4, 6)))
+    b = W.item_pixels_u8(W.C2, 0, (1, 28, 28), src_hw=(300, 500))
+    assert b.shape == (3, 1, 300, 500) and b.min() == 0 and b.max() == 255
+    # neighbouring pixels are correlated (a smooth pattern under the noise)
+    d = np.abs(np.diff(b[0, 0].astype(np.int32), axis=1)).mean()
+    assert d < 0.6 * np.abs(b[0, 0].astype(np.int32) - np.roll(b[0, 0].astype(np.int32), 97, axis=1)).mean()
