@@ -146,6 +146,28 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
                       int32_t num_segments, const int32_t* grid_thw, int32_t num_items,
                       void* out_visual_tokens, void* stream);
 
+/* I_m -> packed patch rows: the step in front of epd_encode (section 3.1: the Encode stage
+ * receives the raw multimodal input I_m, images and video; Eq. 1).  The paper does not say how
+ * I_m becomes encoder input; this library fixes: every frame is resized to the item's grid,
+ * (h * patch) x (w * patch) pixels, by bilinear interpolation with half-pixel centres and the
+ * source coordinate clamped to the image (no antialiasing filter, frames are not resampled in
+ * time, equal sizes copy pixels unchanged); values become (v / 255 - mean[c]) / std[c]; rows
+ * are laid out as epd_encode expects them.
+ *   pixels          device uint8: items packed in order, item i planar
+ *                   [in_channels, t_i * temporal_patch, Hs_i, Ws_i]
+ *   src_hw          HOST int32 [num_items, 2]: (Hs_i, Ws_i), 1 .. 16384 each
+ *   grid_thw        HOST int32 [num_items, 3]: (t, h, w) in patch units; sum t*h*w <= max_tokens
+ *   mean, std       HOST float [in_channels] on the 0..1 pixel scale; std > 0
+ *   packed_patches  device [sum t*h*w, Pdim], cfg.dtype (output; at least 8-byte aligned)
+ *   stream          hipStream_t (NULL = the null stream)
+ * Uses cfg's in_channels (<= 8), patch (even), temporal_patch and dtype; allocates nothing and
+ * touches neither the workspace nor a running epd_encode.  The host arrays are consumed before
+ * the call returns.  Bad metadata returns EPD_ERR_SHAPE / EPD_ERR_INVALID_ARG /
+ * EPD_ERR_UNSUPPORTED with nothing launched. */
+epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* src_hw,
+                          const int32_t* grid_thw, int32_t num_items, const float* mean,
+                          const float* std, void* packed_patches, void* stream);
+
 /* Release host-side state (events, pinned staging).  The workspace stays the caller's. */
 epd_status epd_encode_destroy(epd_handle h);
 

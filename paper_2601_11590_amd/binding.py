@@ -56,7 +56,7 @@ class epd_encode_cfg(C.Structure):
 
 EXPORTS = ["epd_encode_workspace_bytes", "epd_encode_create", "epd_encode", "epd_encode_destroy",
            "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing",
-           "epd_encode_get_timing"]
+           "epd_encode_get_timing", "epd_preprocess"]
 
 
 def _load() -> C.CDLL:
@@ -70,6 +70,9 @@ def _load() -> C.CDLL:
                                C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_void_p]
     lib.epd_encode_destroy.restype = C.c_int
     lib.epd_encode_destroy.argtypes = [C.c_void_p]
+    lib.epd_preprocess.restype = C.c_int
+    lib.epd_preprocess.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
+                                   C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
     lib.epd_encode_last_error.restype = C.c_char_p
     lib.epd_encode_last_error.argtypes = [C.c_void_p]
     lib.epd_encode_debug_hidden.restype = C.c_int
@@ -115,6 +118,20 @@ def epd_encode(handle, packed_patches: int, cu_seqlens: np.ndarray, grid_thw: np
     grid = np.ascontiguousarray(grid_thw, dtype=np.int32).reshape(-1, 3)
     st = lib.epd_encode(handle, packed_patches, cu.ctypes.data_as(C.POINTER(C.c_int32)), len(cu) - 1,
                         grid.ctypes.data_as(C.POINTER(C.c_int32)), grid.shape[0], out_visual_tokens, stream)
+    if st != EPD_OK:
+        raise EpdError(st, epd_encode_last_error(handle))
+
+
+def epd_preprocess(handle, pixels: int, src_hw: np.ndarray, grid_thw: np.ndarray, mean, std,
+                   packed_patches: int, stream: int) -> None:
+    src = np.ascontiguousarray(src_hw, dtype=np.int32).reshape(-1, 2)
+    grid = np.ascontiguousarray(grid_thw, dtype=np.int32).reshape(-1, 3)
+    mu = np.ascontiguousarray(mean, dtype=np.float32)
+    sd = np.ascontiguousarray(std, dtype=np.float32)
+    st = lib.epd_preprocess(handle, pixels, src.ctypes.data_as(C.POINTER(C.c_int32)),
+                            grid.ctypes.data_as(C.POINTER(C.c_int32)), grid.shape[0],
+                            mu.ctypes.data_as(C.POINTER(C.c_float)), sd.ctypes.data_as(C.POINTER(C.c_float)),
+                            packed_patches, stream)
     if st != EPD_OK:
         raise EpdError(st, epd_encode_last_error(handle))
 
@@ -226,6 +243,26 @@ class EpdEncoder:
             stream = torch.cuda.current_stream(self.device).cuda_stream
             epd_encode(self.handle, patches.data_ptr(), cu_seqlens, grid, out.data_ptr(), stream)
         self._last_T = int(patches.shape[0])
+        return out
+
+    def preprocess(self, pixels: torch.Tensor, src_hw, grid_thw, mean, std,
+                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """pixels: device uint8 tensor, items packed in order, each planar [C, t*tp, Hs, Ws].
+        Returns the packed patch rows [T, Pdim] that ``encode`` takes."""
+        assert pixels.is_cuda and pixels.dtype == torch.uint8 and pixels.is_contiguous()
+        grid = np.ascontiguousarray(grid_thw, dtype=np.int32).reshape(-1, 3)
+        src = np.ascontiguousarray(src_hw, dtype=np.int32).reshape(-1, 2)
+        assert len(src) == len(grid) and len(mean) == len(std) == self.cfg.in_channels
+        need = int(sum(self.cfg.in_channels * int(t) * self.cfg.temporal_patch * int(hs) * int(ws)
+                       for (t, _, _), (hs, ws) in zip(grid, src)))
+        assert pixels.numel() >= need, "pixel buffer shorter than the items described"
+        T = int(sum(int(t) * int(h) * int(w) for t, h, w in grid))
+        if out is None:
+            out = torch.empty((T, self.cfg.patch_dim), dtype=self.dtype, device=self.device)
+        assert out.is_cuda and out.dtype == self.dtype and out.is_contiguous() and out.numel() >= T * self.cfg.patch_dim
+        with torch.cuda.device(self.device):
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            epd_preprocess(self.handle, pixels.data_ptr(), src, grid, mean, std, out.data_ptr(), stream)
         return out
 
     def hidden(self) -> torch.Tensor:

@@ -591,6 +591,74 @@ epd_status epd_encode_debug_hidden(epd_handle h, void* out_T_by_D_f32, void* str
   return EPD_OK;
 }
 
+// Raw pixels -> packed patch rows (the step in front of epd_encode).  All checks are made on
+// the host before anything is launched; item descriptors travel as kernel arguments,
+// kPrepItems per launch, so the call touches neither the workspace nor the staging buffers.
+epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* src_hw, const int32_t* grid_thw,
+                          int32_t num_items, const float* mean, const float* stdv, void* packed_patches,
+                          void* stream) {
+  if (!h) { g_create_error = "handle is NULL"; return EPD_ERR_INVALID_ARG; }
+  if (!pixels || !src_hw || !grid_thw || !mean || !stdv || !packed_patches) {
+    h->err = "a required pointer is NULL"; return EPD_ERR_INVALID_ARG;
+  }
+  const epd_encode_cfg& c = h->cfg;
+  if (c.in_channels > kPrepChannels || c.patch % 2) {
+    h->err = fmt("epd_preprocess covers up to %d channels and even patch sizes (have %d, %d)", kPrepChannels,
+                 c.in_channels, c.patch);
+    return EPD_ERR_UNSUPPORTED;
+  }
+  if (num_items <= 0 || num_items > c.max_items) {
+    h->err = fmt("num_items %d (max %d) out of range", num_items, c.max_items); return EPD_ERR_SHAPE;
+  }
+  constexpr int kMaxSide = 16384;     // keeps the tap arithmetic, (2j + 1) * n_in, inside 32 bits
+  for (int ch = 0; ch < c.in_channels; ++ch)
+    if (!(stdv[ch] > 0.f) || !std::isfinite(stdv[ch]) || !std::isfinite(mean[ch])) {
+      h->err = fmt("mean / std of channel %d must be finite, std positive", ch); return EPD_ERR_INVALID_ARG;
+    }
+  int64_t T64 = 0;
+  for (int i = 0; i < num_items; ++i) {
+    const int64_t t = grid_thw[3 * i], hh = grid_thw[3 * i + 1], ww = grid_thw[3 * i + 2];
+    const int64_t hs = src_hw[2 * i], ws = src_hw[2 * i + 1];
+    if (t <= 0 || hh <= 0 || ww <= 0 || hs <= 0 || ws <= 0 || hs > kMaxSide || ws > kMaxSide ||
+        hh * c.patch > kMaxSide || ww * c.patch > kMaxSide) {
+      h->err = fmt("item %d: grid (%lld, %lld, %lld) / source size (%lld, %lld) must be positive, sides at most %d pixels",
+                   i, (long long)t, (long long)hh, (long long)ww, (long long)hs, (long long)ws, kMaxSide);
+      return EPD_ERR_SHAPE;
+    }
+    T64 += t * hh * ww;
+    if (T64 > c.max_tokens) { h->err = fmt("more than max_tokens = %d tokens", c.max_tokens); return EPD_ERR_SHAPE; }
+  }
+  PrepArgs a{};
+  a.pixels = pixels; a.out = packed_patches; a.out_bf16 = c.dtype == EPD_BF16;
+  a.channels = c.in_channels; a.patch = c.patch; a.tp = c.temporal_patch; a.pdim = h->L.pdim;
+  for (int ch = 0; ch < c.in_channels; ++ch) {
+    a.a[ch] = (float)(1.0 / (255.0 * (double)stdv[ch]));
+    a.b[ch] = (float)(-(double)mean[ch] / (double)stdv[ch]);
+  }
+  long long src_off = 0;
+  int tok_off = 0;
+  for (int i0 = 0; i0 < num_items; i0 += kPrepItems) {
+    const int n = std::min(kPrepItems, num_items - i0);
+    long long blocks = 0;
+    for (int j = 0; j < n; ++j) {
+      const int i = i0 + j;
+      PrepItem& d = a.item[j];
+      d.t = grid_thw[3 * i]; d.h = grid_thw[3 * i + 1]; d.w = grid_thw[3 * i + 2];
+      d.hs = src_hw[2 * i]; d.ws = src_hw[2 * i + 1];
+      d.src_off = src_off; d.tok_off = tok_off; d.blk_off = (int)blocks;
+      const long long tokens = (long long)d.t * d.h * d.w;
+      blocks += (tokens * a.pdim / 2 + 255) / 256;
+      src_off += (long long)c.in_channels * d.t * c.temporal_patch * d.hs * d.ws;
+      tok_off += (int)tokens;
+    }
+    if (blocks > 0x7fffffffLL) { h->err = "internal: preprocess grid too large"; return EPD_ERR_SHAPE; }
+    a.n_items = n;
+    launch_preprocess(a, (int)blocks, (hipStream_t)stream);
+  }
+  EPD_HIP(h, hipGetLastError());
+  return EPD_OK;
+}
+
 epd_status epd_encode_set_timing(epd_handle h, int32_t step) {
   if (!h) return EPD_ERR_INVALID_ARG;
   if (step < -1 || step >= EPD_STEP_COUNT) { h->err = "step out of range"; return EPD_ERR_INVALID_ARG; }

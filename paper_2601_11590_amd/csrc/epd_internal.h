@@ -122,6 +122,26 @@ void launch_fold_gamma(void* w, const void* gamma, int N, int K, hipStream_t s);
 void launch_permute_qkv(const void* src_w, const void* src_b, void* dst_w, void* dst_b,
                         int hidden, int num_heads, int head_dim, int elem_bytes, hipStream_t s);
 
+// ---------------------------------------------------------------- raw pixels -> patch rows
+constexpr int kPrepItems = 32;      // items per launch (descriptors travel as kernel arguments)
+constexpr int kPrepChannels = 8;
+struct PrepItem {
+  long long src_off;     // byte offset of the item's first pixel
+  int hs, ws;            // source frame size
+  int t, h, w;           // grid in patches
+  int tok_off;           // first packed row of the item
+  int blk_off;           // first block of the item in this launch
+};
+struct PrepArgs {
+  const uint8_t* pixels;
+  void* out;             // [T, pdim] bf16 or fp32
+  int out_bf16;
+  int n_items, channels, patch, tp, pdim;
+  float a[kPrepChannels], b[kPrepChannels];    // value = pixel * a[c] + b[c]
+  PrepItem item[kPrepItems];
+};
+void launch_preprocess(const PrepArgs& a, int blocks, hipStream_t s);
+
 constexpr int kVtAlign = 128;   // segment starts in the transposed-V buffer are multiples of this
 
 }  // namespace epd

@@ -1,0 +1,149 @@
+"""GPU parity of epd_preprocess (raw uint8 pixels -> packed patch rows, the input I_m of the
+paper's Eq. 1 made ready for the encoder) against the CPU oracle, element by element.
+
+Tolerances.  The kernel computes tap positions exactly (integers) and values in fp32:
+fp32 output: max abs error <= 1e-5 (values are of order 1; three roundings of magnitudes
+<= 255 scaled by 1 / (255 std)); bf16 output: at most one bf16 unit in the last place of the
+fp64 value, |got - ref| <= 2^-8 |ref| + 1e-6 (an fp32 error of 1e-7 can move a value across
+a rounding boundary)."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import preprocess as OP
+from oracle import vit_encode as O
+from paper_2601_11590_amd import binding as B, workloads as W
+from parity_util import check, log
+
+pytestmark = pytest.mark.gpu
+
+MEAN = [0.48145466, 0.4578275, 0.40821073]
+STD = [0.26862954, 0.26130258, 0.27577711]
+
+
+def make(dtype, patch=4, tp=1, **kw):
+    base = dict(name="prep-" + dtype, dtype=dtype, num_layers=1, hidden=128, num_heads=2, head_dim=64, mlp_dim=256,
+                patch=patch, temporal_patch=tp, norm="rmsnorm", rope="2d", rope_pairs=(0, 16, 16), out_dim=64, seed=5)
+    base.update(kw)
+    return W.EncoderConfig(**base)
+
+
+def run(cfg, grids, src, max_items=None):
+    items = [W.item_pixels_u8(cfg, i, g, s) for i, (g, s) in enumerate(zip(grids, src))]
+    T = W.num_tokens(grids)
+    gw = W.global_weights(cfg)
+    layers = [W.layer_weights(cfg, l) for l in range(cfg.num_layers)]
+    enc = B.EpdEncoder(cfg, gw, layers, max_tokens=T, max_segments=len(grids), max_items=max_items or len(grids))
+    flat = np.concatenate([it.ravel() for it in items])
+    px = torch.from_numpy(flat).to("cuda:0")
+    got = enc.preprocess(px, src, grids, MEAN, STD)
+    torch.cuda.synchronize()
+    ref = OP.preprocess(items, grids, cfg.patch, cfg.temporal_patch, MEAN, STD)
+    return enc, got, ref, (gw, layers)
+
+
+def compare(cfg, got, ref):
+    g = got.float().cpu().numpy().astype(np.float64)
+    assert g.shape == ref.shape
+    err = np.abs(g - ref)
+    if cfg.dtype == "f32":
+        log("preprocess f32: max abs err %.3e" % err.max())
+        assert err.max() <= 1e-5
+    else:
+        bound = np.abs(ref) * 2.0 ** -8 + 1e-6
+        log("preprocess bf16: max err / bound %.3f" % (err / bound).max())
+        assert np.all(err <= bound)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_items_upscaled_downscaled_and_untouched(dtype):
+    cfg = make(dtype)
+    grids = [(1, 6, 10), (1, 2, 2), (1, 14, 18), (1, 4, 4), (1, 2, 38)]
+    src = [(24, 40), (5, 7), (100, 31), (16, 16), (9, 300)]        # equal, up, mixed, equal, mixed
+    enc, got, ref, _ = run(cfg, grids, src)
+    compare(cfg, got, ref)
+    enc.close()
+
+
+def test_equal_sizes_give_the_normalised_bytes_themselves():
+    cfg = make("f32", patch=2)
+    grids, src = [(1, 4, 6)], [(8, 12)]
+    enc, got, ref, _ = run(cfg, grids, src)
+    px = W.item_pixels_u8(cfg, 0, grids[0], src[0]).astype(np.float64)
+    want = OP.patch_rows((px / 255.0 - np.array(MEAN)[:, None, None, None]) / np.array(STD)[:, None, None, None], 2, 1)
+    assert np.abs(got.cpu().numpy() - want).max() <= 1e-6
+    enc.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_video_clips_with_two_frames_per_patch_and_patch_14(dtype):
+    cfg = make(dtype, patch=14, tp=2, rope="3d", rope_pairs=(8, 12, 12))
+    grids = [(2, 2, 4), (1, 4, 2), (3, 2, 2)]
+    src = [(30, 50), (56, 28), (17, 90)]
+    enc, got, ref, _ = run(cfg, grids, src)
+    compare(cfg, got, ref)
+    enc.close()
+
+
+def test_more_items_than_one_launch_carries():
+    cfg = make("bf16")
+    rng = np.random.default_rng(3)
+    grids = [(1, 2 * int(rng.integers(1, 4)), 2 * int(rng.integers(1, 4))) for _ in range(75)]
+    src = [(int(rng.integers(3, 40)), int(rng.integers(3, 40))) for _ in grids]
+    enc, got, ref, _ = run(cfg, grids, src)
+    compare(cfg, got, ref)
+    enc.close()
+
+
+def test_c2_batch_of_eight_448_images_from_mixed_source_sizes():
+    cfg = W.C2.replace(num_layers=0)
+    grids = W.grids_for(W.C2)
+    src = [(448, 448), (480, 640), (1080, 1920), (224, 224), (600, 400), (448, 448), (333, 777), (900, 900)]
+    enc, got, ref, _ = run(cfg, grids, src)
+    compare(cfg, got, ref)
+    enc.close()
+
+
+def test_preprocess_then_encode_matches_the_oracle_end_to_end():
+    cfg = make("bf16", num_layers=2)
+    grids = [(1, 6, 10), (1, 8, 4)]
+    src = [(50, 70), (32, 16)]
+    enc, got, ref, (gw, layers) = run(cfg, grids, src)
+    cu, grid = W.metadata(grids)
+    out = enc.encode(got, cu, grid)
+    torch.cuda.synchronize()
+    # the oracle continues from the very rows the library produced (their bf16 values), so the
+    # check isolates the hand-over between the two calls; the rows themselves are checked above
+    rows = got.float().cpu().numpy()
+    want = O.encode(cfg, gw, layers, rows, cu, grid)
+    check(cfg, out.float().cpu().numpy(), want, "output")
+    enc.close()
+
+
+def test_bad_preprocess_arguments_are_rejected_and_the_handle_survives():
+    cfg = make("bf16")
+    grids, src = [(1, 4, 4), (1, 2, 2)], [(16, 16), (8, 8)]
+    enc, got, ref, _ = run(cfg, grids, src)
+    px = torch.zeros(3 * 16 * 16 + 3 * 8 * 8, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty((20, cfg.patch_dim), dtype=torch.bfloat16, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def call(src_hw=src, grid=grids, mean=MEAN, std=STD):
+        B.epd_preprocess(enc.handle, px.data_ptr(), np.array(src_hw), np.array(grid), mean, std, out.data_ptr(), stream)
+
+    for bad in (dict(src_hw=[(0, 16), (8, 8)]), dict(src_hw=[(16, 20000), (8, 8)]), dict(grid=[(1, 4, 4), (1, 0, 2)]),
+                dict(grid=[(1, 4, 4), (1, 2, 4)])):           # the last one: more tokens than max_tokens
+        with pytest.raises(B.EpdError) as e:
+            call(**bad)
+        assert e.value.status == B.EPD_ERR_SHAPE, e.value
+    with pytest.raises(B.EpdError) as e:
+        call(std=[0.2, 0.0, 0.2])
+    assert e.value.status == B.EPD_ERR_INVALID_ARG
+    with pytest.raises(B.EpdError) as e:
+        B.epd_preprocess(enc.handle, px.data_ptr(), np.array(src + src), np.array(grids + grids), MEAN, STD, out.data_ptr(), stream)
+    assert e.value.status == B.EPD_ERR_SHAPE                 # more items than max_items
+    call()                                                     # still works
+    torch.cuda.synchronize()
+    compare(cfg, out, OP.preprocess([np.zeros((3, 1, 16, 16), np.uint8), np.zeros((3, 1, 8, 8), np.uint8)], grids, 4, 1, MEAN, STD))
+    enc.close()
