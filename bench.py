@@ -152,6 +152,39 @@ def main():
         % (ms_per_step, value, flops_call / (ms_per_step * 1e-3) / 1e12,
            100 * flops_call / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS))
 
+    # ---- the step in front of the path (raw uint8 pixels -> packed patch rows), timed on its
+    # own: it is not part of `value`, whose inputs are the packed rows already in HBM
+    prep = None
+    if cfg.patch % 2 == 0:
+        src = [(int(h) * cfg.patch, int(w) * cfg.patch) for _, h, w in grids]
+        px = torch.from_numpy(np.concatenate([W.item_pixels_u8(cfg, i, g, s).ravel()
+                                              for i, (g, s) in enumerate(zip(grids, src))])).to("cuda:0")
+        rows = torch.empty_like(p_dev)
+        mean, std = [0.5] * cfg.in_channels, [0.25] * cfg.in_channels
+        for _ in range(3):
+            enc.preprocess(px, src, grids, mean, std, out=rows)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 50
+        # a few milliseconds of unrelated GPU work go first, so that the host has queued all the
+        # launches by the time the first one runs and the events bracket kernel time only
+        blocker = torch.ones((8192, 8192), dtype=torch.bfloat16, device="cuda:0")
+        torch.cuda.synchronize()
+        for _ in range(8):
+            blocker @ blocker
+        e0.record()
+        for _ in range(reps):
+            enc.preprocess(px, src, grids, mean, std, out=rows)
+        e1.record()
+        torch.cuda.synchronize()
+        del blocker
+        p_ms = e0.elapsed_time(e1) / reps
+        p_bytes = px.numel() + rows.numel() * rows.element_size()
+        prep = {"ms": p_ms, "bytes": p_bytes, "achieved_GBs": p_bytes / (p_ms * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
+                "frac": p_bytes / (p_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bound": "hbm",
+                "note": "epd_preprocess, sources at grid size (no resize); mean of %d launches queued back to back" % reps}
+        log("[bench] epd_preprocess: %.4f ms per call, %.1f MB -> %.0f GB/s" % (p_ms, p_bytes / 1e6, prep["achieved_GBs"]))
+        del px, rows
+
     gpu_out = out.float().cpu().numpy()
     cpu = None
     if args.cpu_items > 0:
@@ -181,6 +214,7 @@ def main():
                      "launches": dom_n, "avg_launch_ms": dom_ms / max(dom_n, 1),
                      "flops_per_launch": dom_work / max(dom_n, 1)},
         "cpu_baseline": cpu,
+        "preprocess": prep,
         "steps_ms": {k: v[0] for k, v in table.items() if v[1] > 0},
     }
     enc.close()

@@ -160,7 +160,7 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
  *   mean, std       HOST float [in_channels] on the 0..1 pixel scale; std > 0
  *   packed_patches  device [sum t*h*w, Pdim], cfg.dtype (output; at least 8-byte aligned)
  *   stream          hipStream_t (NULL = the null stream)
- * Uses cfg's in_channels (<= 8), patch (even), temporal_patch and dtype; allocates nothing and
+ * Uses cfg's in_channels (<= 8), patch (even, <= 32), temporal_patch and dtype; allocates nothing and
  * touches neither the workspace nor a running epd_encode.  The host arrays are consumed before
  * the call returns.  Bad metadata returns EPD_ERR_SHAPE / EPD_ERR_INVALID_ARG /
  * EPD_ERR_UNSUPPORTED with nothing launched. */

@@ -602,8 +602,8 @@ epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* sr
     h->err = "a required pointer is NULL"; return EPD_ERR_INVALID_ARG;
   }
   const epd_encode_cfg& c = h->cfg;
-  if (c.in_channels > kPrepChannels || c.patch % 2) {
-    h->err = fmt("epd_preprocess covers up to %d channels and even patch sizes (have %d, %d)", kPrepChannels,
+  if (c.in_channels > kPrepChannels || c.patch % 2 || c.patch > 32 || c.in_channels * c.temporal_patch > 65535) {
+    h->err = fmt("epd_preprocess covers up to %d channels and even patch sizes up to 32 (have %d, %d)", kPrepChannels,
                  c.in_channels, c.patch);
     return EPD_ERR_UNSUPPORTED;
   }
@@ -647,7 +647,7 @@ epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* sr
       d.hs = src_hw[2 * i]; d.ws = src_hw[2 * i + 1];
       d.src_off = src_off; d.tok_off = tok_off; d.blk_off = (int)blocks;
       const long long tokens = (long long)d.t * d.h * d.w;
-      blocks += (tokens * a.pdim / 2 + 255) / 256;
+      blocks += tokens;
       src_off += (long long)c.in_channels * d.t * c.temporal_patch * d.hs * d.ws;
       tok_off += (int)tokens;
     }

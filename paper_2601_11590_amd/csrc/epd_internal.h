@@ -130,7 +130,7 @@ struct PrepItem {
   int hs, ws;            // source frame size
   int t, h, w;           // grid in patches
   int tok_off;           // first packed row of the item
-  int blk_off;           // first block of the item in this launch
+  int blk_off;           // first token of the item in this launch (blockIdx.x counts tokens)
 };
 struct PrepArgs {
   const uint8_t* pixels;
@@ -140,7 +140,7 @@ struct PrepArgs {
   float a[kPrepChannels], b[kPrepChannels];    // value = pixel * a[c] + b[c]
   PrepItem item[kPrepItems];
 };
-void launch_preprocess(const PrepArgs& a, int blocks, hipStream_t s);
+void launch_preprocess(const PrepArgs& a, int tokens, hipStream_t s);   // patch <= 32 (block = patch/2 x patch)
 
 constexpr int kVtAlign = 128;   // segment starts in the transposed-V buffer are multiples of this
 

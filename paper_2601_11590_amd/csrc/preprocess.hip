@@ -28,44 +28,75 @@ __device__ __forceinline__ Tap tap(int j, int n_in, int n_out) {
   return t;
 }
 
-__global__ __launch_bounds__(256) void preprocess_kernel(PrepArgs a) {
-  // which item this block works on (at most kPrepItems, ascending block offsets)
+// One block = one token (one output row): thread (x, y) makes V neighbouring elements of row y
+// of each of the token's channel x frame slabs of patch x patch elements in turn, so every pass
+// writes patch * patch consecutive elements and nothing about an element's position has to be
+// divided out of a flat index.  V = 8 (one 16-byte bf16 store) when the patch size allows it,
+// else 2.  blockIdx.x counts the tokens of the (at most kPrepItems) items of this launch.
+template <int V>
+__global__ __launch_bounds__(512) void preprocess_kernel(PrepArgs a) {
   int it = 0;
   while (it + 1 < a.n_items && (int)blockIdx.x >= a.item[it + 1].blk_off) ++it;
   const PrepItem d = a.item[it];
-  const long long e = ((long long)(blockIdx.x - d.blk_off) * 256 + threadIdx.x) * 2;   // element pair inside the item
-  const long long n_el = (long long)d.t * d.h * d.w * a.pdim;
-  if (e >= n_el) return;
   const int p = a.patch;
-  const int tok = (int)(e / a.pdim), k = (int)(e - (long long)tok * a.pdim);
-  const int px = k % p, py = (k / p) % p, dt = (k / (p * p)) % a.tp, c = k / (p * p * a.tp);
+  const int tok = blockIdx.x - d.blk_off;                 // token inside the item
   const int col = tok % d.w, row = (tok / d.w) % d.h, ti = tok / (d.w * d.h);
+  const int px = threadIdx.x * V, py = threadIdx.y;
   const int ho = d.h * p, wo = d.w * p;
-  const Tap ty = tap(row * p + py, d.hs, ho);
-  const Tap tx0 = tap(col * p + px, d.ws, wo), tx1 = tap(col * p + px + 1, d.ws, wo);
-  const uint8_t* f = a.pixels + d.src_off + ((long long)c * (d.t * a.tp) + (ti * a.tp + dt)) * ((long long)d.hs * d.ws);
-  const uint8_t* r0 = f + (long long)ty.i0 * d.ws;
-  const uint8_t* r1 = f + (long long)ty.i1 * d.ws;
-  auto sample = [&](const Tap& tx) {
-    const float top = (1.0f - tx.w1) * (float)r0[tx.i0] + tx.w1 * (float)r0[tx.i1];
-    const float bot = (1.0f - tx.w1) * (float)r1[tx.i0] + tx.w1 * (float)r1[tx.i1];
-    return fmaf((1.0f - ty.w1) * top + ty.w1 * bot, a.a[c], a.b[c]);
-  };
-  const float v0 = sample(tx0), v1 = sample(tx1);
-  const long long o = (long long)d.tok_off * a.pdim + e;
-  if (a.out_bf16) {
-    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-    bf16x2 v;
-    v[0] = (__bf16)v0; v[1] = (__bf16)v1;
-    *(bf16x2*)((uint16_t*)a.out + o) = v;
-  } else {
-    *(float2*)((float*)a.out + o) = make_float2(v0, v1);
+  const int y = row * p + py, x = col * p + px;
+  const long long plane = (long long)d.hs * d.ws;
+  const bool same = d.hs == ho && d.ws == wo;             // no resize: the taps are the pixels themselves
+  Tap ty = {y, y, 0.f}, tx[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) tx[i] = Tap{x + i, x + i, 0.f};
+  if (!same) {
+    ty = tap(y, d.hs, ho);
+#pragma unroll
+    for (int i = 0; i < V; ++i) tx[i] = tap(x + i, d.ws, wo);
+  }
+  const long long o_row = (long long)(d.tok_off + tok) * a.pdim + py * p + px;
+  for (int c = 0; c < a.channels; ++c) {
+    const float ac = a.a[c], bc = a.b[c];
+    for (int dt = 0; dt < a.tp; ++dt) {
+      const uint8_t* f = a.pixels + d.src_off + ((long long)c * (d.t * a.tp) + (ti * a.tp + dt)) * plane;
+      const uint8_t* r0 = f + (long long)ty.i0 * d.ws;
+      float v[V];
+      if (same) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] = fmaf((float)r0[x + i], ac, bc);
+      } else {
+        const uint8_t* r1 = f + (long long)ty.i1 * d.ws;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const float top = (1.0f - tx[i].w1) * (float)r0[tx[i].i0] + tx[i].w1 * (float)r0[tx[i].i1];
+          const float bot = (1.0f - tx[i].w1) * (float)r1[tx[i].i0] + tx[i].w1 * (float)r1[tx[i].i1];
+          v[i] = fmaf((1.0f - ty.w1) * top + ty.w1 * bot, ac, bc);
+        }
+      }
+      const long long o = o_row + (long long)(c * a.tp + dt) * p * p;
+      if (a.out_bf16) {
+        typedef __attribute__((ext_vector_type(V))) __bf16 bf16xV;
+        bf16xV w;
+#pragma unroll
+        for (int i = 0; i < V; ++i) w[i] = (__bf16)v[i];
+        *(bf16xV*)((uint16_t*)a.out + o) = w;
+      } else {
+        typedef __attribute__((ext_vector_type(V))) float f32xV;
+        f32xV w;
+#pragma unroll
+        for (int i = 0; i < V; ++i) w[i] = v[i];
+        *(f32xV*)((float*)a.out + o) = w;
+      }
+    }
   }
 }
 
-void launch_preprocess(const PrepArgs& a, int blocks, hipStream_t s) {
-  if (blocks <= 0) return;
-  hipLaunchKernelGGL(preprocess_kernel, dim3(blocks), dim3(256), 0, s, a);
+void launch_preprocess(const PrepArgs& a, int tokens, hipStream_t s) {
+  if (tokens <= 0) return;
+  // 16-byte stores need the rows (pdim = C * tp * patch^2 elements) and the buffer 16-byte aligned
+  const bool wide = a.patch % 8 == 0 && ((size_t)a.out & (a.out_bf16 ? 15 : 31)) == 0;
+  if (wide) hipLaunchKernelGGL(preprocess_kernel<8>, dim3(tokens), dim3(a.patch / 8, a.patch), 0, s, a);
+  else hipLaunchKernelGGL(preprocess_kernel<2>, dim3(tokens), dim3(a.patch / 2, a.patch), 0, s, a);
 }
 
 }  // namespace epd

@@ -66,6 +66,16 @@ def test_ragged_items_upscaled_downscaled_and_untouched(dtype):
     enc.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_patch_sizes_that_take_the_16_byte_store_path(dtype):
+    cfg = make(dtype, patch=8)
+    grids = [(1, 4, 6), (1, 2, 2), (1, 6, 2)]
+    src = [(32, 48), (11, 23), (100, 9)]                          # equal, up, mixed
+    enc, got, ref, _ = run(cfg, grids, src)
+    compare(cfg, got, ref)
+    enc.close()
+
+
 def test_equal_sizes_give_the_normalised_bytes_themselves():
     cfg = make("f32", patch=2)
     grids, src = [(1, 4, 6)], [(8, 12)]
