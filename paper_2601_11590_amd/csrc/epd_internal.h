@@ -46,7 +46,7 @@ struct GemmArgs {
   int vt_stride;
   const int32_t* vcol;  // [M] column of token m in vt
   const void* zeros;    // bf16 path: >= 16 readable zero bytes (source of out-of-range tile chunks)
-  int overread_ok;      // bf16 path: 1 = rows [M, round_up(M, 256)) of A and [N, round_up(N, 256)) of
+  int overread_ok;      // bf16 path: 1 = rows [M, round_up(M, 320)) of A and [N, round_up(N, 256)) of
                         //   W are readable memory (contents irrelevant): enables the load path
                         //   without per-lane row clamping
   // bf16 path, RMSNorm folded into the GEMMs around it (see launch_fold_gamma):
