@@ -252,3 +252,32 @@ def test_c5_full_video_batch_one_layer_last_clip_against_oracle():
     cu1, g1 = W.metadata(grids[3:])
     ref = O.encode(cfg, gw, layers, patches[3 * n:], cu1, g1)
     check(cfg, got[3 * nm:], ref, "clip 4 of 4, 8192 tokens")
+
+
+def test_c3_full_depth_varlen_batch_smallest_images_against_oracle():
+    """The largest batch of the benchmark configurations at its full depth (32 images of mixed
+    sizes, 73 896 tokens, 24 layers) in one call; the oracle recomputes the three smallest
+    images alone, which block-diagonal attention makes equal to their rows in the batch."""
+    from paper_2601_11590_amd import binding as B
+    import torch
+    cfg = W.C3
+    grids = W.grids_for(cfg)
+    log("case %s: 32 images, %d tokens, L=%d; oracle on the three smallest" % (cfg.name, W.num_tokens(grids), cfg.num_layers))
+    gw, layers = W.all_weights(cfg)
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids)
+    enc = B.EpdEncoder(cfg, gw, layers, max_tokens=patches.shape[0], max_segments=len(grids), max_items=len(grids))
+    try:
+        got = enc.encode(B.to_device_patches(patches, cfg.dtype), cu, grid)
+        torch.cuda.synchronize()
+        got = got.float().cpu().numpy()
+    finally:
+        enc.close()
+    assert got.shape == (W.num_merged_tokens(grids), cfg.out_dim) and np.isfinite(got).all()
+    toks = [t * h * w for t, h, w in grids]
+    tok_off = np.concatenate([[0], np.cumsum(toks)])
+    for item in np.argsort(toks, kind="stable")[:3]:
+        cu1, g1 = W.metadata([grids[item]])
+        ref = O.encode(cfg, gw, layers, patches[tok_off[item]:tok_off[item + 1]], cu1, g1)
+        m0 = tok_off[item] // 4
+        check(cfg, got[m0:m0 + toks[item] // 4], ref, "image %d (%d tokens) of 32, 24 layers" % (item, toks[item]))
