@@ -40,6 +40,7 @@ extern "C" {
 typedef struct epd_encoder* epd_handle;
 
 typedef enum {
+  EPD_MISS = 1,             /* epd_store_lookup only: key not present (not a failure)          */
   EPD_OK = 0,
   EPD_ERR_INVALID_ARG = -1, /* NULL pointer, bad enum value, bad struct_size            */
   EPD_ERR_UNSUPPORTED = -2, /* a shape the kernels do not cover (see epd_encode_create)  */
@@ -167,6 +168,69 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
 epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* src_hw,
                           const int32_t* grid_thw, int32_t num_items, const float* mean,
                           const float* std, void* packed_patches, void* stream);
+
+/* ---- single-node stand-in for the MM Store (section 3.2) -------------------------------
+ * "Multimodal Cache Pooling": encoded features are stored under the hash of the multimodal
+ * input, so that a repeated input is not encoded again; "Fault-Tolerant and Recomputation": a
+ * feature that cannot be fetched is recomputed.  The paper names neither the hash nor the
+ * pool's replacement rule; this library fixes:
+ *   key    two polynomial hashes modulo P = 2^61 - 1 with bases R_0 = 0x1D4E2C1B3A596877 mod P,
+ *          R_1 = 0x0F1E2D3C4B5A6978 mod P over the words s_0 .. s_{L-1} = byte length (low,
+ *          high 32 bits), salt (low, high), then the input as 32-bit little-endian words (last
+ *          one zero-padded):  H_k = sum_j (s_j + 1) * R_k^(L - j) mod P.
+ *   pool   caller-owned device memory; the first 1 MiB is scratch for the hash, the rest an
+ *          arena of contiguous, 256-byte aligned entries; an insert drops least-recently-used
+ *          entries until a free range (first fit, lowest address) holds the new entry; a
+ *          lookup that hits makes its entry the most recent.
+ * One call per store at a time.  Bookkeeping (create / lookup / insert / stats / destroy) is
+ * host code and never touches device memory. */
+typedef struct epd_store* epd_store_handle;
+
+/* device_pool: device, 256-byte aligned, pool_bytes > 1 MiB; owned by the caller, must outlive
+ * the store.  *out is written only on success. */
+epd_status epd_store_create(void* device_pool, uint64_t pool_bytes, epd_store_handle* out);
+epd_status epd_store_destroy(epd_store_handle s);
+/* Message of the last failure on this store (of the last failed create when s == NULL). */
+const char* epd_store_last_error(epd_store_handle s);
+
+/* Keys of n byte ranges of one device buffer: range i = [offsets[i], offsets[i+1]) (HOST
+ * uint64 [n + 1], non-decreasing, each range < 8 GiB), salts HOST uint64 [n], keys_out HOST
+ * uint64 [n, 2].  Launches on `stream` and waits for the keys. */
+epd_status epd_store_hash(epd_store_handle s, const void* device_data, const uint64_t* offsets,
+                          const uint64_t* salts, int32_t n, uint64_t* keys_out, void* stream);
+
+/* EPD_OK: *device_ptr / *bytes describe the stored value (valid until a later insert drops
+ * it); EPD_MISS: not stored.  `bytes` may be NULL. */
+epd_status epd_store_lookup(epd_store_handle s, const uint64_t key[2], void** device_ptr,
+                            uint64_t* bytes);
+/* Reserve `bytes` for `key` (replacing an entry of the same key) and return where the caller
+ * must write the value, in stream order before any reader.  EPD_ERR_WORKSPACE (nothing
+ * dropped) when the entry can never fit. */
+epd_status epd_store_insert(epd_store_handle s, const uint64_t key[2], uint64_t bytes,
+                            void** device_ptr);
+/* Counters since create; any pointer may be NULL. */
+epd_status epd_store_stats(epd_store_handle s, uint64_t* hits, uint64_t* misses,
+                           uint64_t* evictions, uint64_t* entries);
+
+/* V_m = E(I_m) through the store: every item (image / clip) is keyed by the hash of its pixels,
+ * salted with its source size, grid, the patch geometry, dtype and `model_salt` (which must
+ * identify the weights):  x = model_salt; for f in (Hs, Ws, t, h, w, patch, temporal_patch,
+ * in_channels, dtype): x = (x ^ (uint64)f) * 0x9E3779B97F4A7C15 mod 2^64.  Items found in the
+ * store are copied from it; the others are preprocessed (epd_preprocess), encoded together in
+ * one epd_encode call with one attention segment per item, filed in the store and copied to
+ * their rows of out_visual_tokens.  Arguments as in epd_preprocess / epd_encode, plus
+ *   rows_scratch   device [sum t*h*w, Pdim], cfg.dtype: patch rows of the items that miss
+ *   out_scratch    device [sum merged tokens, out_dim], cfg.dtype: their rows before filing
+ *   hit_out        HOST int32 [num_items] or NULL: 1 = served from the store
+ *   keys_out       HOST uint64 [num_items, 2] or NULL
+ * Waits on `stream` once (for the keys); everything else is asynchronous on it.  An item too
+ * large for the pool is encoded and returned but not stored. */
+epd_status epd_encode_cached(epd_handle h, epd_store_handle s, uint64_t model_salt,
+                             const uint8_t* pixels, const int32_t* src_hw,
+                             const int32_t* grid_thw, int32_t num_items, const float* mean,
+                             const float* std, void* rows_scratch, void* out_scratch,
+                             void* out_visual_tokens, int32_t* hit_out, uint64_t* keys_out,
+                             void* stream);
 
 /* Release host-side state (events, pinned staging).  The workspace stays the caller's. */
 epd_status epd_encode_destroy(epd_handle h);

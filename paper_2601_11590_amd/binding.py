@@ -18,6 +18,7 @@ import torch
 from . import build as _build
 
 EPD_OK, EPD_ERR_INVALID_ARG, EPD_ERR_UNSUPPORTED, EPD_ERR_SHAPE, EPD_ERR_WORKSPACE, EPD_ERR_HIP = 0, -1, -2, -3, -4, -5
+EPD_MISS = 1
 EPD_F32, EPD_BF16 = 0, 1
 EPD_LAYERNORM, EPD_RMSNORM = 0, 1
 EPD_GELU_ERF, EPD_GELU_TANH = 0, 1
@@ -56,7 +57,9 @@ class epd_encode_cfg(C.Structure):
 
 EXPORTS = ["epd_encode_workspace_bytes", "epd_encode_create", "epd_encode", "epd_encode_destroy",
            "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing",
-           "epd_encode_get_timing", "epd_preprocess"]
+           "epd_encode_get_timing", "epd_preprocess", "epd_encode_cached", "epd_store_create",
+           "epd_store_destroy", "epd_store_last_error", "epd_store_hash", "epd_store_lookup", "epd_store_insert",
+           "epd_store_stats"]
 
 
 def _load() -> C.CDLL:
@@ -70,6 +73,24 @@ def _load() -> C.CDLL:
                                C.POINTER(C.c_int32), C.c_int32, C.c_void_p, C.c_void_p]
     lib.epd_encode_destroy.restype = C.c_int
     lib.epd_encode_destroy.argtypes = [C.c_void_p]
+    U64P, I32P, F32P = C.POINTER(C.c_uint64), C.POINTER(C.c_int32), C.POINTER(C.c_float)
+    lib.epd_store_create.restype = C.c_int
+    lib.epd_store_create.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p)]
+    lib.epd_store_destroy.restype = C.c_int
+    lib.epd_store_destroy.argtypes = [C.c_void_p]
+    lib.epd_store_last_error.restype = C.c_char_p
+    lib.epd_store_last_error.argtypes = [C.c_void_p]
+    lib.epd_store_hash.restype = C.c_int
+    lib.epd_store_hash.argtypes = [C.c_void_p, C.c_void_p, U64P, U64P, C.c_int32, U64P, C.c_void_p]
+    lib.epd_store_lookup.restype = C.c_int
+    lib.epd_store_lookup.argtypes = [C.c_void_p, U64P, C.POINTER(C.c_void_p), U64P]
+    lib.epd_store_insert.restype = C.c_int
+    lib.epd_store_insert.argtypes = [C.c_void_p, U64P, C.c_uint64, C.POINTER(C.c_void_p)]
+    lib.epd_store_stats.restype = C.c_int
+    lib.epd_store_stats.argtypes = [C.c_void_p, U64P, U64P, U64P, U64P]
+    lib.epd_encode_cached.restype = C.c_int
+    lib.epd_encode_cached.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, I32P, I32P, C.c_int32, F32P, F32P,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, I32P, U64P, C.c_void_p]
     lib.epd_preprocess.restype = C.c_int
     lib.epd_preprocess.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32,
                                    C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
@@ -134,6 +155,92 @@ def epd_preprocess(handle, pixels: int, src_hw: np.ndarray, grid_thw: np.ndarray
                             packed_patches, stream)
     if st != EPD_OK:
         raise EpdError(st, epd_encode_last_error(handle))
+
+
+class StoreError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("epd store status %d: %s" % (status, message))
+        self.status = status
+
+
+def epd_store_last_error(store: Optional[int]) -> str:
+    return lib.epd_store_last_error(store).decode()
+
+
+def epd_store_create(pool_ptr: int, pool_bytes: int) -> int:
+    s = C.c_void_p()
+    st = lib.epd_store_create(pool_ptr, pool_bytes, C.byref(s))
+    if st != EPD_OK:
+        raise StoreError(st, epd_store_last_error(None))
+    return s.value
+
+
+def epd_store_destroy(store) -> None:
+    lib.epd_store_destroy(store)
+
+
+def _key(key):
+    return (C.c_uint64 * 2)(int(key[0]), int(key[1]))
+
+
+def epd_store_lookup(store, key):
+    """(device pointer, bytes) of a stored value, or None."""
+    p, n = C.c_void_p(), C.c_uint64()
+    st = lib.epd_store_lookup(store, _key(key), C.byref(p), C.byref(n))
+    if st == EPD_MISS:
+        return None
+    if st != EPD_OK:
+        raise StoreError(st, epd_store_last_error(store))
+    return p.value, n.value
+
+
+def epd_store_insert(store, key, nbytes: int) -> int:
+    p = C.c_void_p()
+    st = lib.epd_store_insert(store, _key(key), nbytes, C.byref(p))
+    if st != EPD_OK:
+        raise StoreError(st, epd_store_last_error(store))
+    return p.value
+
+
+def epd_store_stats(store):
+    v = [C.c_uint64() for _ in range(4)]
+    st = lib.epd_store_stats(store, *[C.byref(x) for x in v])
+    if st != EPD_OK:
+        raise StoreError(st, epd_store_last_error(store))
+    return dict(zip(("hits", "misses", "evictions", "entries"), (x.value for x in v)))
+
+
+def epd_store_hash(store, data_ptr: int, offsets, salts, stream: int) -> np.ndarray:
+    """uint64 [n, 2] keys of the byte ranges [offsets[i], offsets[i+1]) of one device buffer."""
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    sa = np.ascontiguousarray(salts, dtype=np.uint64)
+    n = len(sa)
+    assert len(off) == n + 1
+    keys = np.zeros((n, 2), dtype=np.uint64)
+    U64P = C.POINTER(C.c_uint64)
+    st = lib.epd_store_hash(store, data_ptr, off.ctypes.data_as(U64P), sa.ctypes.data_as(U64P), n,
+                            keys.ctypes.data_as(U64P), stream)
+    if st != EPD_OK:
+        raise StoreError(st, epd_store_last_error(store))
+    return keys
+
+
+def epd_encode_cached(handle, store, model_salt: int, pixels: int, src_hw, grid_thw, mean, std, rows_scratch: int,
+                      out_scratch: int, out_visual_tokens: int, stream: int):
+    """Returns (hit flags int32 [items], keys uint64 [items, 2])."""
+    src = np.ascontiguousarray(src_hw, dtype=np.int32).reshape(-1, 2)
+    grid = np.ascontiguousarray(grid_thw, dtype=np.int32).reshape(-1, 3)
+    mu = np.ascontiguousarray(mean, dtype=np.float32)
+    sd = np.ascontiguousarray(std, dtype=np.float32)
+    hit = np.zeros(grid.shape[0], dtype=np.int32)
+    keys = np.zeros((grid.shape[0], 2), dtype=np.uint64)
+    I32P, F32P, U64P = C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_uint64)
+    st = lib.epd_encode_cached(handle, store, model_salt, pixels, src.ctypes.data_as(I32P), grid.ctypes.data_as(I32P),
+                               grid.shape[0], mu.ctypes.data_as(F32P), sd.ctypes.data_as(F32P), rows_scratch, out_scratch,
+                               out_visual_tokens, hit.ctypes.data_as(I32P), keys.ctypes.data_as(U64P), stream)
+    if st != EPD_OK:
+        raise EpdError(st, epd_encode_last_error(handle))
+    return hit, keys
 
 
 def epd_encode_destroy(handle) -> None:
@@ -265,6 +372,33 @@ class EpdEncoder:
             epd_preprocess(self.handle, pixels.data_ptr(), src, grid, mean, std, out.data_ptr(), stream)
         return out
 
+    def encode_cached(self, store: "MMStore", model_salt: int, pixels: torch.Tensor, src_hw, grid_thw, mean, std,
+                      out: Optional[torch.Tensor] = None):
+        """Raw pixels -> visual tokens through the store.  Returns (out, hit flags, keys)."""
+        assert pixels.is_cuda and pixels.dtype == torch.uint8 and pixels.is_contiguous()
+        grid = np.ascontiguousarray(grid_thw, dtype=np.int32).reshape(-1, 3)
+        src = np.ascontiguousarray(src_hw, dtype=np.int32).reshape(-1, 2)
+        assert len(src) == len(grid)
+        need = int(sum(self.cfg.in_channels * int(t) * self.cfg.temporal_patch * int(hs) * int(ws)
+                       for (t, _, _), (hs, ws) in zip(grid, src)))
+        assert pixels.numel() >= need, "pixel buffer shorter than the items described"
+        m = self.cfg.merge
+        T = int(sum(int(t) * int(h) * int(w) for t, h, w in grid))
+        tm = int(sum(int(t) * (int(h) // m) * (int(w) // m) for t, h, w in grid))
+        rows = torch.empty((max(T, 1), self.cfg.patch_dim), dtype=self.dtype, device=self.device)
+        tmp = torch.empty((max(tm, 1), self.cfg.out_dim), dtype=self.dtype, device=self.device)
+        if out is None:
+            out = torch.empty((tm, self.cfg.out_dim), dtype=self.dtype, device=self.device)
+        assert out.is_cuda and out.dtype == self.dtype and out.is_contiguous() and out.numel() >= tm * self.cfg.out_dim
+        with torch.cuda.device(self.device):
+            stream = torch.cuda.current_stream(self.device).cuda_stream
+            hit, keys = epd_encode_cached(self.handle, store.handle, model_salt, pixels.data_ptr(), src, grid, mean, std,
+                                          rows.data_ptr(), tmp.data_ptr(), out.data_ptr(), stream)
+            # the scratch tensors are read by work queued on this stream: keep them until it is through
+            rows.record_stream(torch.cuda.current_stream(self.device))
+            tmp.record_stream(torch.cuda.current_stream(self.device))
+        return out, hit, keys
+
     def hidden(self) -> torch.Tensor:
         """fp32 residual stream [T, D] of the last call (before the final norm)."""
         out = torch.empty((self._last_T, self.cfg.hidden), dtype=torch.float32, device=self.device)
@@ -282,6 +416,38 @@ class EpdEncoder:
         if self.handle is not None:
             torch.cuda.synchronize(self.device)
             epd_encode_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class MMStore:
+    """Device pool + the library's store handle (single-node stand-in for the paper's MM Store)."""
+
+    def __init__(self, pool_bytes: int, device: str = "cuda:0"):
+        self.device = torch.device(device)
+        self.pool = torch.empty(pool_bytes + 256, dtype=torch.uint8, device=self.device)
+        base = (self.pool.data_ptr() + 255) // 256 * 256
+        self.base = base
+        self.handle = epd_store_create(base, pool_bytes)
+
+    def hash(self, data: torch.Tensor, offsets, salts) -> np.ndarray:
+        assert data.is_cuda and data.dtype == torch.uint8 and data.is_contiguous()
+        assert int(np.asarray(offsets)[-1]) <= data.numel()
+        with torch.cuda.device(self.device):
+            return epd_store_hash(self.handle, data.data_ptr(), offsets, salts, torch.cuda.current_stream(self.device).cuda_stream)
+
+    def stats(self):
+        return epd_store_stats(self.handle)
+
+    def close(self) -> None:
+        if self.handle is not None:
+            torch.cuda.synchronize(self.device)
+            epd_store_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

@@ -591,19 +591,13 @@ epd_status epd_encode_debug_hidden(epd_handle h, void* out_T_by_D_f32, void* str
   return EPD_OK;
 }
 
-// Raw pixels -> packed patch rows (the step in front of epd_encode).  All checks are made on
-// the host before anything is launched; item descriptors travel as kernel arguments,
-// kPrepItems per launch, so the call touches neither the workspace nor the staging buffers.
-epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* src_hw, const int32_t* grid_thw,
-                          int32_t num_items, const float* mean, const float* stdv, void* packed_patches,
-                          void* stream) {
-  if (!h) { g_create_error = "handle is NULL"; return EPD_ERR_INVALID_ARG; }
-  if (!pixels || !src_hw || !grid_thw || !mean || !stdv || !packed_patches) {
-    h->err = "a required pointer is NULL"; return EPD_ERR_INVALID_ARG;
-  }
+// Checks shared by the entry points that take raw pixels: everything that decides how far a
+// kernel reads or writes is validated here, on the host, before anything is launched.
+static epd_status check_raw_items(epd_handle h, const int32_t* src_hw, const int32_t* grid_thw, int32_t num_items,
+                                  const float* mean, const float* stdv, bool for_encode) {
   const epd_encode_cfg& c = h->cfg;
   if (c.in_channels > kPrepChannels || c.patch % 2 || c.patch > 32 || c.in_channels * c.temporal_patch > 65535) {
-    h->err = fmt("epd_preprocess covers up to %d channels and even patch sizes up to 32 (have %d, %d)", kPrepChannels,
+    h->err = fmt("raw-pixel input covers up to %d channels and even patch sizes up to 32 (have %d, %d)", kPrepChannels,
                  c.in_channels, c.patch);
     return EPD_ERR_UNSUPPORTED;
   }
@@ -625,9 +619,31 @@ epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* sr
                    i, (long long)t, (long long)hh, (long long)ww, (long long)hs, (long long)ws, kMaxSide);
       return EPD_ERR_SHAPE;
     }
+    if (for_encode && (hh % c.merge || ww % c.merge)) {
+      h->err = fmt("item %d: h, w must be divisible by merge %d", i, c.merge); return EPD_ERR_SHAPE;
+    }
     T64 += t * hh * ww;
     if (T64 > c.max_tokens) { h->err = fmt("more than max_tokens = %d tokens", c.max_tokens); return EPD_ERR_SHAPE; }
   }
+  if (for_encode && num_items > c.max_segments) {
+    h->err = fmt("one attention segment per item: %d items exceed max_segments = %d", num_items, c.max_segments);
+    return EPD_ERR_SHAPE;
+  }
+  return EPD_OK;
+}
+
+// Raw pixels -> packed patch rows (the step in front of epd_encode).  All checks are made on
+// the host before anything is launched; item descriptors travel as kernel arguments,
+// kPrepItems per launch, so the call touches neither the workspace nor the staging buffers.
+epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* src_hw, const int32_t* grid_thw,
+                          int32_t num_items, const float* mean, const float* stdv, void* packed_patches,
+                          void* stream) {
+  if (!h) { g_create_error = "handle is NULL"; return EPD_ERR_INVALID_ARG; }
+  if (!pixels || !src_hw || !grid_thw || !mean || !stdv || !packed_patches) {
+    h->err = "a required pointer is NULL"; return EPD_ERR_INVALID_ARG;
+  }
+  const epd_encode_cfg& c = h->cfg;
+  if (epd_status st = check_raw_items(h, src_hw, grid_thw, num_items, mean, stdv, false)) return st;
   PrepArgs a{};
   a.pixels = pixels; a.out = packed_patches; a.out_bf16 = c.dtype == EPD_BF16;
   a.channels = c.in_channels; a.patch = c.patch; a.tp = c.temporal_patch; a.pdim = h->L.pdim;
@@ -656,6 +672,85 @@ epd_status epd_preprocess(epd_handle h, const uint8_t* pixels, const int32_t* sr
     launch_preprocess(a, (int)blocks, (hipStream_t)stream);
   }
   EPD_HIP(h, hipGetLastError());
+  return EPD_OK;
+}
+
+// Encode through the store (see the header): hash -> lookup -> copy the hits, preprocess and
+// encode the misses as one compact batch, file them, copy them out.  Everything after the
+// keys have arrived is asynchronous on one stream, so a pool range that an insert of this
+// call recycles is overwritten only after the copies that still read it.
+epd_status epd_encode_cached(epd_handle h, epd_store_handle s, uint64_t model_salt, const uint8_t* pixels,
+                             const int32_t* src_hw, const int32_t* grid_thw, int32_t num_items, const float* mean,
+                             const float* stdv, void* rows_scratch, void* out_scratch, void* out_visual_tokens,
+                             int32_t* hit_out, uint64_t* keys_out, void* stream) {
+  if (!h) { g_create_error = "handle is NULL"; return EPD_ERR_INVALID_ARG; }
+  if (!s || !pixels || !src_hw || !grid_thw || !mean || !stdv || !rows_scratch || !out_scratch || !out_visual_tokens) {
+    h->err = "a required pointer is NULL"; return EPD_ERR_INVALID_ARG;
+  }
+  if (epd_status st = check_raw_items(h, src_hw, grid_thw, num_items, mean, stdv, true)) return st;
+  const epd_encode_cfg& c = h->cfg;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t es = h->L.es, row_bytes = (size_t)c.out_dim * es;
+  const int n = num_items;
+  std::vector<uint64_t> off(n + 1, 0), salt(n), keys((size_t)n * 2);
+  std::vector<int64_t> tok(n + 1, 0), mrg(n + 1, 0);
+  for (int i = 0; i < n; ++i) {
+    const int64_t t = grid_thw[3 * i], hh = grid_thw[3 * i + 1], ww = grid_thw[3 * i + 2];
+    const int64_t hs = src_hw[2 * i], ws = src_hw[2 * i + 1];
+    off[i + 1] = off[i] + (uint64_t)(c.in_channels * t * c.temporal_patch * hs * ws);
+    tok[i + 1] = tok[i] + t * hh * ww;
+    mrg[i + 1] = mrg[i] + t * (hh / c.merge) * (ww / c.merge);
+    uint64_t x = model_salt;
+    const int64_t f[9] = {hs, ws, t, hh, ww, c.patch, c.temporal_patch, c.in_channels, (int64_t)c.dtype};
+    for (int64_t v : f) x = (x ^ (uint64_t)v) * 0x9E3779B97F4A7C15ull;
+    salt[i] = x;
+  }
+  if (epd_status e = epd_store_hash(s, pixels, off.data(), salt.data(), n, keys.data(), stream)) {
+    h->err = std::string("epd_store_hash: ") + epd_store_last_error(s); return e;
+  }
+  if (keys_out) std::memcpy(keys_out, keys.data(), keys.size() * 8);
+  // hits: copy out; misses: collect
+  std::vector<int> miss;
+  for (int i = 0; i < n; ++i) {
+    void* p = nullptr;
+    uint64_t bytes = 0;
+    const size_t want = (size_t)(mrg[i + 1] - mrg[i]) * row_bytes;
+    const epd_status e = epd_store_lookup(s, &keys[2 * i], &p, &bytes);
+    const bool hit = e == EPD_OK && bytes == want;
+    if (hit_out) hit_out[i] = hit ? 1 : 0;
+    if (hit) EPD_HIP(h, hipMemcpyAsync((char*)out_visual_tokens + (size_t)mrg[i] * row_bytes, p, want, hipMemcpyDeviceToDevice, st));
+    else miss.push_back(i);
+  }
+  if (miss.empty()) return EPD_OK;
+  // misses: preprocess every run of neighbouring items into the compact batch, then encode it
+  std::vector<int32_t> cu(miss.size() + 1, 0), grid(miss.size() * 3);
+  const size_t prow = (size_t)h->L.pdim * es;
+  for (size_t k = 0; k < miss.size();) {
+    size_t e = k + 1;
+    while (e < miss.size() && miss[e] == miss[e - 1] + 1) ++e;
+    const int i0 = miss[k], cnt = (int)(e - k);
+    if (epd_status stt = epd_preprocess(h, pixels + off[i0], src_hw + 2 * i0, grid_thw + 3 * i0, cnt, mean, stdv,
+                                        (char*)rows_scratch + (size_t)cu[k] * prow, stream)) return stt;
+    for (size_t j = k; j < e; ++j) {
+      const int i = miss[j];
+      cu[j + 1] = cu[j] + (int32_t)(tok[i + 1] - tok[i]);
+      grid[3 * j] = grid_thw[3 * i]; grid[3 * j + 1] = grid_thw[3 * i + 1]; grid[3 * j + 2] = grid_thw[3 * i + 2];
+    }
+    k = e;
+  }
+  if (epd_status stt = epd_encode(h, rows_scratch, cu.data(), (int32_t)miss.size(), grid.data(), (int32_t)miss.size(),
+                                  out_scratch, stream)) return stt;
+  size_t m0 = 0;
+  for (size_t j = 0; j < miss.size(); ++j) {
+    const int i = miss[j];
+    const size_t bytes = (size_t)(mrg[i + 1] - mrg[i]) * row_bytes;
+    const char* src = (const char*)out_scratch + m0 * row_bytes;
+    EPD_HIP(h, hipMemcpyAsync((char*)out_visual_tokens + (size_t)mrg[i] * row_bytes, src, bytes, hipMemcpyDeviceToDevice, st));
+    void* slot = nullptr;
+    if (epd_store_insert(s, &keys[2 * i], bytes, &slot) == EPD_OK)
+      EPD_HIP(h, hipMemcpyAsync(slot, src, bytes, hipMemcpyDeviceToDevice, st));
+    m0 += (size_t)(mrg[i + 1] - mrg[i]);
+  }
   return EPD_OK;
 }
 
