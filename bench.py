@@ -155,6 +155,7 @@ def main():
     # ---- the step in front of the path (raw uint8 pixels -> packed patch rows), timed on its
     # own: it is not part of `value`, whose inputs are the packed rows already in HBM
     prep = None
+    store_res = None
     if cfg.patch % 2 == 0:
         src = [(int(h) * cfg.patch, int(w) * cfg.patch) for _, h, w in grids]
         px = torch.from_numpy(np.concatenate([W.item_pixels_u8(cfg, i, g, s).ravel()
@@ -183,6 +184,34 @@ def main():
                 "frac": p_bytes / (p_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bound": "hbm",
                 "note": "epd_preprocess, sources at grid size (no resize); mean of %d launches queued back to back" % reps}
         log("[bench] epd_preprocess: %.4f ms per call, %.1f MB -> %.0f GB/s" % (p_ms, p_bytes / 1e6, prep["achieved_GBs"]))
+        # ---- the step behind it: the feature store (hash of the input as key; a hit skips the encoder)
+        if args.config == "C2" and args.layers is None:
+            store = B.MMStore((1 << 20) + 2 * out.numel() * out.element_size())
+            offs = np.concatenate([[0], np.cumsum([cfg.in_channels * t * cfg.temporal_patch * hs * ws
+                                                   for (t, _, _), (hs, ws) in zip(grids, src)])]).astype(np.uint64)
+            for _ in range(2):
+                store.hash(px, offs, [1] * len(grids))
+            t0 = time.perf_counter()
+            for _ in range(20):
+                store.hash(px, offs, [1] * len(grids))
+            h_ms = (time.perf_counter() - t0) / 20 * 1e3           # includes the wait for the 128 bytes of keys
+            t0 = time.perf_counter()
+            _, hit_a, _ = enc.encode_cached(store, 7, px, src, grids, mean, std)
+            torch.cuda.synchronize()
+            miss_ms = (time.perf_counter() - t0) * 1e3
+            t0 = time.perf_counter()
+            for _ in range(10):
+                _, hit_b, _ = enc.encode_cached(store, 7, px, src, grids, mean, std)
+            torch.cuda.synchronize()
+            hit_ms = (time.perf_counter() - t0) / 10 * 1e3
+            assert not hit_a.any() and hit_b.all()
+            store_res = {"hash_ms_per_call_incl_sync": h_ms, "hash_bytes": int(px.numel()),
+                         "all_miss_call_ms": miss_ms, "all_hit_call_ms": hit_ms,
+                         "note": "epd_store_hash of the 8 images (one launch pair + key copy + wait); "
+                                 "epd_encode_cached on raw pixels: first call (preprocess + encode + file) vs repeated call"}
+            log("[bench] mm store: hash %.3f ms per call (%.1f MB, waits for the keys); encode_cached all-miss %.3f ms, all-hit %.3f ms"
+                % (h_ms, px.numel() / 1e6, miss_ms, hit_ms))
+            store.close()
         del px, rows
 
     gpu_out = out.float().cpu().numpy()
@@ -215,6 +244,7 @@ def main():
                      "flops_per_launch": dom_work / max(dom_n, 1)},
         "cpu_baseline": cpu,
         "preprocess": prep,
+        "mm_store": store_res,
         "steps_ms": {k: v[0] for k, v in table.items() if v[1] > 0},
     }
     enc.close()
