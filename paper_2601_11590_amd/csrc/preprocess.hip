@@ -35,11 +35,16 @@ __device__ __forceinline__ Tap tap(int j, int n_in, int n_out) {
 // else 2.  blockIdx.x counts the tokens of the (at most kPrepItems) items of this launch.
 template <int V>
 __global__ __launch_bounds__(512) void preprocess_kernel(PrepArgs a) {
+  // consecutive block ids go to different XCDs (8, each with its own L2): give every XCD a
+  // contiguous eighth of the tokens, so that the neighbouring patches that share a 128-byte line
+  // of source pixels fetch it through one L2 instead of eight
+  const int nb = gridDim.x;
+  const int vb = (blockIdx.x & 7) * (nb >> 3) + min((int)(blockIdx.x & 7), nb & 7) + (blockIdx.x >> 3);
   int it = 0;
-  while (it + 1 < a.n_items && (int)blockIdx.x >= a.item[it + 1].blk_off) ++it;
+  while (it + 1 < a.n_items && vb >= a.item[it + 1].blk_off) ++it;
   const PrepItem d = a.item[it];
   const int p = a.patch;
-  const int tok = blockIdx.x - d.blk_off;                 // token inside the item
+  const int tok = vb - d.blk_off;                         // token inside the item
   const int col = tok % d.w, row = (tok / d.w) % d.h, ti = tok / (d.w * d.h);
   const int px = threadIdx.x * V, py = threadIdx.y;
   const int ho = d.h * p, wo = d.w * p;
