@@ -626,6 +626,16 @@ __global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g)
   gemm_tile<T, EPI, OUT, false, GATHER, FAST>(g, m0, n0, lds);
 }
 
+static int num_cus() {
+  static int n = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    return v;
+  }();
+  return n;
+}
+
 template <class T, int EPI, int OUT, bool GATHER>
 static void launch_cfg(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + T::BM - 1) / T::BM, tiles_n = (g.N + T::BN - 1) / T::BN;
@@ -634,6 +644,12 @@ static void launch_cfg(const GemmArgs& g, hipStream_t s) {
     // keep the A panels of one group (group_m x BM rows x K) within about 2 MB of the 4 MB L2
     const long panel = (long)T::BM * g.K * 2;
     a.group_m = (int)std::max(1L, std::min((long)tiles_m, (2L << 20) / std::max(panel, 1L)));
+    // Few rows against a large weight matrix (the merger projection): with row groups every
+    // XCD streams all of W.  When the whole grid runs in at most two rounds, number the tiles
+    // column by column instead, so that an XCD owns a block of columns: W is then fetched
+    // once in total and the (smaller) A once per XCD.
+    const long blocks = (long)T::MINBLK * num_cus();
+    if ((long)g.N > 2L * g.M && (long)tiles_m * tiles_n <= 2 * blocks) a.group_m = tiles_m;
   }
   a.group_m = std::min(a.group_m, tiles_m);
   if constexpr (!GATHER) {
@@ -656,16 +672,6 @@ using T5 = Tile<320, 256, 64, 2, 4, 1>;   // 8 waves, 160x64 wave tiles, 144 KB 
 static int forced_tile() {
   const char* e = getenv("EPD_GEMM_TILE");
   return e ? atoi(e) : -1;
-}
-
-static int num_cus() {
-  static int n = [] {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-      v = 256;
-    return v;
-  }();
-  return n;
 }
 
 // Tile choice.  The 256 x 256 tile halves the operand traffic per flop and is the fastest
