@@ -56,6 +56,73 @@ def cpu_baseline(cfg, gw, layers, patches, cu, grid, gpu_out, n_items):
             "seconds": dt, "parity_min_cos": float(cos.min()), "parity_max_rel": float(rel.max())}
 
 
+def colocation():
+    """Operator-level co-location (paper section 3.5, "Physical Co-Location and Spatial Multiplexing"):
+    how much one kind of work slows down when another kind runs beside it on the same GPU, for work
+    bound by different units.  Rows = the measured operator, columns = the neighbour; entries =
+    time beside the neighbour / time alone.  Prints one JSON line."""
+    import torch
+    from paper_2601_11590_amd import binding as B, workloads as W
+    cfg = W.C2
+    grids = W.grids_for(cfg)
+    T, Tm = W.num_tokens(grids), W.num_merged_tokens(grids, cfg.merge)
+    gw = W.global_weights(cfg)
+    layers = [W.layer_weights(cfg, l) for l in range(cfg.num_layers)]
+    patches = B.to_device_patches(W.packed_patches(cfg, grids), cfg.dtype)
+    cu, grid = W.metadata(grids)
+    encs = [B.EpdEncoder(cfg, gw, layers, max_tokens=T, max_segments=len(grids), max_items=len(grids)) for _ in range(2)]
+    outs = [torch.empty((Tm, cfg.out_dim), dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]
+    src = [torch.ones(1 << 27, dtype=torch.float32, device="cuda:0") for _ in range(2)]     # 512 MiB each
+    dst = [torch.empty_like(x) for x in src]
+    stores = [B.MMStore(2 << 20) for _ in range(2)]
+    blob = [torch.randint(0, 256, (64 << 20,), dtype=torch.uint8, device="cuda:0") for _ in range(2)]
+    nrm = [torch.randn((1 << 16, 1024), dtype=torch.float32, device="cuda:0") for _ in range(2)]
+
+    # one unit of each kind of work, on the current stream; slot 0 = measured, 1 = neighbour
+    ops = {
+        "encode (matrix cores + exp)": lambda i: encs[i].encode(patches, cu, grid, outs[i]),
+        "copy 512 MiB (HBM)": lambda i: dst[i].copy_(src[i]),
+        "hash 64 MiB (integer ALU)": lambda i: stores[i].hash(blob[i], [0, blob[i].numel()], [1]),
+        "softmax 64k x 1024 fp32 (HBM + exp)": lambda i: torch.softmax(nrm[i], dim=-1),
+    }
+    # the hash call waits for its keys (it is synchronous by contract), so it cannot sit in a queue
+    # beside something else: it is measured, never a neighbour
+    names = list(ops)
+    neighbours = [n for n in names if not n.startswith("hash")]
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    reps = {"encode (matrix cores + exp)": 6, "copy 512 MiB (HBM)": 60, "hash 64 MiB (integer ALU)": 20,
+            "softmax 64k x 1024 fp32 (HBM + exp)": 60}
+
+    def timed(a, b):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if b is not None:
+            with torch.cuda.stream(s2):
+                for _ in range(reps[b] * 6):          # a queue several times longer than the measured run
+                    ops[b](1)
+        with torch.cuda.stream(s1):
+            ops[a](0)
+            e0.record()
+            for _ in range(reps[a]):
+                ops[a](0)
+            e1.record()
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / reps[a]
+        torch.cuda.synchronize()
+        return ms
+
+    alone = {a: min(timed(a, None) for _ in range(2)) for a in names}
+    table = {a: {b: timed(a, b) / alone[a] for b in neighbours} for a in names}
+    for a in names:
+        log("[colocation] %-38s alone %8.3f ms | " % (a, alone[a]) + "  ".join("beside %s: x%.2f" % (b.split(" (")[0], table[a][b]) for b in neighbours))
+    print(json.dumps({"experiment": "operator co-location slowdown (time beside neighbour / time alone), one MI355X, two streams of default priority",
+                      "alone_ms": alone, "slowdown": table}), flush=True)
+    for e in encs:
+        e.close()
+    for st in stores:
+        st.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -66,7 +133,16 @@ def main():
     ap.add_argument("--cpu-items", type=int, default=8, help="images of the batch the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--in-flight", type=int, default=1,
+                    help="batches in flight on separate streams (serving mode; default 1 = one stream)")
+    ap.add_argument("--colocation", action="store_true",
+                    help="only run the operator co-location experiment (section 3.5) and print its table")
     args = ap.parse_args()
+    if args.colocation:
+        if args.gpus != 1:
+            log("bench.py: one GPU only"); sys.exit(2)
+        colocation()
+        return
     if args.copy_calibration:
         import torch
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
@@ -131,15 +207,34 @@ def main():
     dom_id = B.STEP_NAMES.index(dom)
 
     # ---- timed region: exactly K steps; the dominant kernel is bracketed by HIP events
+    # --in-flight N > 1: N encoders (own workspace and output each) on N streams of default
+    # priority take the steps in turn, so that kernels of different batches fill each other's
+    # idle compute units; the default, 1, is the plain sequence of calls on one stream
+    extra = []
+    if args.in_flight > 1:
+        for _ in range(args.in_flight - 1):
+            extra.append((B.EpdEncoder(cfg, gw, layers, max_tokens=T, max_segments=len(cu) - 1, max_items=len(grids)),
+                          torch.empty_like(out), torch.cuda.Stream()))
+        for e, o, st in extra:
+            with torch.cuda.stream(st):
+                e.encode(p_dev, cu, grid, o)
+        torch.cuda.synchronize()
+    lanes = [(enc, out, torch.cuda.current_stream())] + extra
     enc.set_timing(dom_id)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        enc.encode(p_dev, cu, grid, out)
+    for i in range(args.steps):
+        e, o, st = lanes[i % len(lanes)]
+        with torch.cuda.stream(st):
+            e.encode(p_dev, cu, grid, o)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     dom_ms, dom_n, dom_work = enc.get_timing()
     enc.set_timing(-1)
+    if extra:
+        assert all(torch.equal(o, out) for _, o, _ in extra), "batches in flight disagree"
+        for e, _, _ in extra:
+            e.close()
 
     ms_per_step = dt / args.steps * 1e3
     value = Tm * args.steps / dt
@@ -235,7 +330,7 @@ def main():
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "%s: %d layers, D=%d, %dx%d heads, MLP %d, patch %d, %d items, %d patch tokens -> %d visual tokens"
                                % (cfg.name, L, D, cfg.num_heads, cfg.head_dim, F, cfg.patch, len(grids), T, Tm),
-                   "patch_tokens": T, "visual_tokens": Tm, "patch_tokens_per_s": T * args.steps / dt,
+                   "batches_in_flight": args.in_flight, "patch_tokens": T, "visual_tokens": Tm, "patch_tokens_per_s": T * args.steps / dt,
                    "tflops_end_to_end": flops_call / (ms_per_step * 1e-3) / 1e12,
                    "mfma_util_pct_end_to_end": 100 * flops_call / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -316,7 +316,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     const float ss = ((st_a.x + st_a.y) + (st_a.z + st_a.w)) + ((st_b.x + st_b.y) + (st_b.z + st_b.w));
     row_scale[tid] = 1.0f / sqrtf(fmaf(ss, g.stats_inv_dim, g.stats_eps));
   }
-  if (nk > 1 && !(g.tile_cfg & 256)) issue_step(1, 1);
+  if (nk > 1) issue_step(1, 1);
   read_frags(I0{}, I0{}, I0{});
 
   auto step = [&](auto S, int kt) {
@@ -338,16 +338,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
           const unsigned long long c0 = __builtin_readcyclecounter();
           wait_vmcnt<0>();
           const unsigned long long c1 = __builtin_readcyclecounter();
-          if (!(g.tile_cfg & 512)) __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_s_barrier();
           const unsigned long long c2 = __builtin_readcyclecounter();
           tr_vm += c1 - c0; tr_bar += c2 - c1;
 #else
           wait_vmcnt<0>();
           wait_frags(I1{}, I0{});
-          if (!(g.tile_cfg & 512)) __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_s_barrier();
 #endif
           if constexpr (!LATE_REFILL) {
-            if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(s, kt + 2);
+            if (kt + 2 < nk) issue_step(s, kt + 2);
           }
           read_frags(I0{}, SN{}, I0{});
         } else {
@@ -359,7 +359,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
           // address arithmetic and load instructions run in their shadow (pinning this order
           // costs registers, which the large wave tiles do not have)
           __builtin_amdgcn_sched_barrier(0);
-          if (kt + 2 < nk && !(g.tile_cfg & 256)) issue_step(s, kt + 2);
+          if (kt + 2 < nk) issue_step(s, kt + 2);
           __builtin_amdgcn_sched_barrier(0);
         }
       }

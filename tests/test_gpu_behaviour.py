@@ -281,3 +281,33 @@ def test_c3_full_depth_varlen_batch_smallest_images_against_oracle():
         ref = O.encode(cfg, gw, layers, patches[tok_off[item]:tok_off[item + 1]], cu1, g1)
         m0 = tok_off[item] // 4
         check(cfg, got[m0:m0 + toks[item] // 4], ref, "image %d (%d tokens) of 32, 24 layers" % (item, toks[item]))
+
+
+def test_batches_in_flight_on_separate_streams_equal_the_single_stream_result():
+    """Serving mode of bench.py (--in-flight): several encoders, each with its own workspace, take
+    batches in turn on streams of their own, so kernels of different batches overlap on the GPU.
+    Every call must return exactly what the same call returns alone."""
+    from paper_2601_11590_amd import binding as B
+    import torch
+    cfg = W.C2.replace(num_layers=3)
+    grids = W.grids_for(W.C2)
+    gw, layers = W.all_weights(cfg)
+    patches = B.to_device_patches(W.packed_patches(cfg, grids), cfg.dtype)
+    other = B.to_device_patches(W.packed_patches(cfg, grids, seed=123), cfg.dtype)
+    cu, grid = W.metadata(grids)
+    encs = [B.EpdEncoder(cfg, gw, layers, max_tokens=patches.shape[0], max_segments=8, max_items=8) for _ in range(3)]
+    try:
+        alone = [encs[0].encode(p, cu, grid).clone() for p in (patches, other)]
+        torch.cuda.synchronize()
+        streams = [torch.cuda.Stream() for _ in encs]
+        outs = []
+        for rep in range(4):
+            for i, (e, st) in enumerate(zip(encs, streams)):
+                with torch.cuda.stream(st):
+                    outs.append(((rep + i) % 2, e.encode(other if (rep + i) % 2 else patches, cu, grid).clone()))
+        torch.cuda.synchronize()
+        for which, o in outs:
+            assert torch.equal(o, alone[which])
+    finally:
+        for e in encs:
+            e.close()
