@@ -219,7 +219,8 @@ def main():
             with torch.cuda.stream(st):
                 e.encode(p_dev, cu, grid, o)
         torch.cuda.synchronize()
-    lanes = [(enc, out, torch.cuda.current_stream())] + extra
+    # with several lanes none of them is the default stream (whose launches order against the others')
+    lanes = [(enc, out, torch.cuda.Stream() if extra else torch.cuda.current_stream())] + extra
     enc.set_timing(dom_id)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
