@@ -53,6 +53,11 @@ def build(verbose: bool = False, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=min(len(SOURCES), 8)) as ex:
         list(ex.map(one, zip(SOURCES, objs)))
+    # the kernels that wait for inline LDS reads by hand: prove on the generated code that the
+    # compiler moved no register while a read into it was pending (see check_lds_waits.py)
+    from . import check_lds_waits
+    check_lds_waits.check_sources(hipcc, [*FLAGS, *extra_flags],
+                                  [os.path.join(CSRC, s) for s in ("gemm_bf16.hip", "attn_bf16.hip")])
     out = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose and out.strip():
         print(out)

@@ -63,8 +63,14 @@ template <int OFF> __device__ __forceinline__ void lds_read16(bf16x8& d, uint32_
 template <int OFF> __device__ __forceinline__ void lds_read8(u32x2& d, uint32_t addr) {
   asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
 }
+// The compiler takes the result of an inline ds_read for valid at once; the ties that follow a
+// wait keep the consumers behind it, and the scheduling barrier keeps any register copy the
+// compiler makes for a tie behind it as well (a copy hoisted above the wait would read a
+// register the LDS has not filled yet).  The generated code is checked for such copies at
+// build time (check_lds_waits.py).
 template <int PENDING> __device__ __forceinline__ void lds_wait() {
   asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(PENDING) : "memory");
+  __builtin_amdgcn_sched_barrier(0);
 }
 __device__ __forceinline__ void tie(bf16x8& f) { asm volatile("" : "+v"(f)); }
 

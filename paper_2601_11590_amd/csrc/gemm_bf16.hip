@@ -102,8 +102,14 @@ template <int N, int STRIDE, int BASE, int I = 0> __device__ __forceinline__ voi
 }
 // wait until at most PENDING LDS reads of this wave are outstanding (they return in order),
 // then tie the N fragments to the wait so that their consumers cannot be scheduled above it
+// The compiler takes the result of an inline ds_read for valid at once: the ties keep the
+// consumers behind the wait, and the scheduling barrier keeps any register copy the compiler
+// makes for a tie behind it as well -- a copy hoisted above the wait reads a register the LDS
+// has not filled yet (seen once, with a variant of the main loop; the generated code of every
+// kernel is checked for such copies at build time, check_lds_waits.py).
 template <int PENDING, int N> __device__ __forceinline__ void wait_lds_reads(bf16x8* f) {
   asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(PENDING) : "memory");
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
 }
@@ -300,6 +306,26 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
 
+  // Residual rows this thread updates in the epilogue (EPI_RESIDUAL, where its whole share is
+  // at most 16 float4): fetched behind the last stage hand-over, so that the read of the
+  // residual stream overlaps the last K step instead of standing at the head of the epilogue.
+  // Rows and columns beyond the matrix are clamped (what they fetch is not used).
+  constexpr int E_HALF = BN / T::EPI_PASSES, E_LPR4 = E_HALF / 4, E_RPS = NT / E_LPR4, E_SW = BM / E_RPS;
+  constexpr bool PREF = EPI == EPI_RESIDUAL && !VMODE && T::EPI_PASSES * E_SW <= 16;
+  [[maybe_unused]] float4 xpre[PREF ? T::EPI_PASSES * E_SW : 1];
+  auto prefetch_resid = [&]() {
+    if constexpr (PREF) {
+#pragma unroll
+      for (int h = 0; h < T::EPI_PASSES; ++h)
+#pragma unroll
+        for (int sw = 0; sw < E_SW; ++sw) {
+          const int m = min(m0 + sw * E_RPS + tid / E_LPR4, g.M - 1);
+          const int n = min(n0 + h * E_HALF + (tid % E_LPR4) * 4, g.N - 4);
+          xpre[h * E_SW + sw] = *(const float4*)(g.resid + (size_t)m * g.ldr + n);
+        }
+    }
+  };
+
   // ---- main loop: two LDS stages.  The hand-over to the next stage happens before the last
   // 16-wide k slice of the current stage is multiplied: wait for the own loads of stage s^1,
   // barrier (everybody's loads landed, everybody finished reading stage s), refill stage s
@@ -350,6 +376,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
             if (kt + 2 < nk) issue_step(s, kt + 2);
           }
           read_frags(I0{}, SN{}, I0{});
+          if (kt + 2 >= nk) prefetch_resid();          // last hand-over: no operand load follows
         } else {
           wait_frags(I1{}, I0{});
         }
@@ -369,6 +396,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     step(I0{}, kt);
     if (kt + 1 < nk) step(I1{}, kt + 1);
   }
+  if (nk == 1) prefetch_resid();
 
 #ifdef EPD_GEMM_TRACE
   const unsigned long long tr_loop_end = __builtin_readcyclecounter();
@@ -436,64 +464,76 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         }
       }
     }
-  } else if constexpr ((EPI == EPI_STORE || EPI == EPI_GELU) && OUT == OUT_BF16 && BM * (BN * 2 + 16) <= T::LDS_BYTES) {
-    // bf16 output with a per-element epilogue: scale, bias and activation are applied in the
-    // MFMA layout (a lane holds 4 consecutive columns of one token), the results are staged as
-    // bf16 -- the whole tile in one pass, half the LDS traffic of the fp32 staging below -- and
-    // leave as 16-byte row-contiguous stores.
-    constexpr int ROWO = BN * 2 + 16;                  // padded: 16 consecutive rows hit 16 different bank groups
-    static_assert(BM * ROWO <= T::LDS_BYTES, "bf16 staging area");
+  } else if constexpr ((EPI == EPI_STORE || EPI == EPI_GELU) && OUT == OUT_BF16) {
+    // bf16 output with a per-element epilogue that needs nothing but the element and its
+    // column: scale, bias and activation are applied in the MFMA layout (a lane holds 4
+    // consecutive columns of one token) and the finished bf16 values are staged through LDS,
+    // the whole tile at once where it fits and in two column halves where not, to leave as
+    // 16-byte row-contiguous stores.  Half the LDS traffic of the fp32 staging below, all waves
+    // write at the same time, one or two passes instead of two or four.  (The rotary epilogue
+    // stays on the fp32 path: its cos / sin table is read row by row there; read from the MFMA
+    // layout, 32 rows per load instruction, it measured 25 % slower.)
+    constexpr int NP = BM * (BN * 2 + 16) <= T::LDS_BYTES ? 1 : 2;   // passes
+    constexpr int CP = BN / NP;                                      // columns per pass
+    constexpr int ROWO = CP * 2 + 16;                  // padded: 16 consecutive rows hit 16 different bank groups
+    static_assert(BM * ROWO <= T::LDS_BYTES && CP % WN == 0, "bf16 staging area");
+    constexpr int CPRO = CP / 8, RPSO = NT / CPRO;     // 16-byte chunks per row, rows per sweep
+    static_assert(BM % RPSO == 0, "sweeps");
     float rsv[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) rsv[i] = 1.0f;
-    __syncthreads();
-    if (scaled) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i) rsv[i] = row_scale[wm * WM + i * 32 + l32];
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nl = wn * WN + j * 32 + q * 8 + lg * 4;
-        float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
-        if (bias && n0 + nl < g.N) {                   // N is a multiple of 4: all or nothing
-          const uint2 bb = *(const uint2*)(bias + n0 + nl);
-          b0 = bf16_bits_to_float(bb.x & 0xffff); b1 = bf16_bits_to_float(bb.x >> 16);
-          b2 = bf16_bits_to_float(bb.y & 0xffff); b3 = bf16_bits_to_float(bb.y >> 16);
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int ml = wm * WM + i * 32 + l32;
-          float v0 = fmaf(acc[i][j][4 * q], rsv[i], b0), v1 = fmaf(acc[i][j][4 * q + 1], rsv[i], b1);
-          float v2 = fmaf(acc[i][j][4 * q + 2], rsv[i], b2), v3 = fmaf(acc[i][j][4 * q + 3], rsv[i], b3);
-          if constexpr (EPI == EPI_GELU) {
-            if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
-            else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
-          }
-          *(uint2*)(lds + ml * ROWO + nl * 2) = pack_bf16x4(v0, v1, v2, v3);
-        }
-      }
-    __syncthreads();
-    constexpr int CPRO = BN / 8, RPSO = NT / CPRO;     // 16-byte chunks per row, rows per sweep
-    static_assert(BM % RPSO == 0, "sweeps");
-    const int c8 = (tid % CPRO) * 8;
-    const int n = n0 + c8;
     uint16_t* const outp = (uint16_t*)g.out;
-    const bool vec = (g.ldo % 8 == 0) && (((size_t)outp & 15) == 0) && n + 8 <= g.N;
-    if (n < g.N) {
+    const int c8 = (tid % CPRO) * 8;
 #pragma unroll
-      for (int sw = 0; sw < BM / RPSO; ++sw) {
-        const int r = sw * RPSO + tid / CPRO;
-        const int m = m0 + r;
-        if (m >= g.M) continue;
-        const uint4 v = *(const uint4*)(lds + r * ROWO + c8 * 2);
-        uint16_t* dst = outp + (size_t)m * g.ldo + n;
-        if (vec) {
-          *(uint4*)dst = v;
-        } else {
-          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-          for (int t = 0; t < 8 && n + t < g.N; ++t) dst[t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
+    for (int ps = 0; ps < NP; ++ps) {
+      __syncthreads();
+      if (ps == 0 && scaled) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) rsv[i] = row_scale[wm * WM + i * 32 + l32];
+      }
+      if ((wn * WN) / CP == ps) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int nl = wn * WN + j * 32 + q * 8 + lg * 4;      // column inside the tile
+            const int n = n0 + nl;
+            float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+            if (bias && n < g.N) {                       // N is a multiple of 4: all or nothing
+              const uint2 bb = *(const uint2*)(bias + n);
+              b0 = bf16_bits_to_float(bb.x & 0xffff); b1 = bf16_bits_to_float(bb.x >> 16);
+              b2 = bf16_bits_to_float(bb.y & 0xffff); b3 = bf16_bits_to_float(bb.y >> 16);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+              const int ml = wm * WM + i * 32 + l32;
+              float v0 = fmaf(acc[i][j][4 * q], rsv[i], b0), v1 = fmaf(acc[i][j][4 * q + 1], rsv[i], b1);
+              float v2 = fmaf(acc[i][j][4 * q + 2], rsv[i], b2), v3 = fmaf(acc[i][j][4 * q + 3], rsv[i], b3);
+              if constexpr (EPI == EPI_GELU) {
+                if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
+                else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
+              }
+              *(uint2*)(lds + ml * ROWO + (nl - ps * CP) * 2) = pack_bf16x4(v0, v1, v2, v3);
+            }
+          }
+      }
+      __syncthreads();
+      const int n = n0 + ps * CP + c8;
+      const bool vec = (g.ldo % 8 == 0) && (((size_t)outp & 15) == 0) && n + 8 <= g.N;
+      if (n < g.N) {
+#pragma unroll
+        for (int sw = 0; sw < BM / RPSO; ++sw) {
+          const int r = sw * RPSO + tid / CPRO;
+          const int m = m0 + r;
+          if (m >= g.M) continue;
+          const uint4 v = *(const uint4*)(lds + r * ROWO + c8 * 2);
+          uint16_t* dst = outp + (size_t)m * g.ldo + n;
+          if (vec) {
+            *(uint4*)dst = v;
+          } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            for (int t = 0; t < 8 && n + t < g.N; ++t) dst[t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
+          }
         }
       }
     }
@@ -558,7 +598,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         }
         if constexpr (EPI == EPI_RESIDUAL) {
           float4* xp = (float4*)(g.resid + (size_t)m * g.ldr + n);
-          float4 x = *xp;
+          float4 x;
+          if constexpr (PREF) x = xpre[h * E_SW + sw];
+          else x = *xp;
           x.x += v0; x.y += v1; x.z += v2; x.w += v3;
           *xp = x;
           // folded RMSNorm (producer side): the raw rows in bf16 for the next GEMM, and their
