@@ -16,7 +16,9 @@ operations complete in order, so ``lgkmcnt(N)`` retires the oldest LDS entries b
 youngest N (scalar loads may complete out of order: each one in the queue is assumed to have
 taken one of the completions the wait guarantees).  Where paths with different queues meet they
 are aligned at the youngest entry and united position by position.  Queues are cut to the 16
-operations the hardware counter can hold.
+operations the hardware counter can hold.  A register that a later instruction overwrites leaves
+the pending sets: what is checked is a copy of a value that has not arrived, not the reuse of a
+register.
 """
 
 from __future__ import annotations
@@ -175,6 +177,13 @@ def check_function(name: str, first_line: int, body: List[str]) -> List[str]:
                         else:
                             kept.append(e)
                     q = kept
+            if ins.dst and not ins.op.startswith(("ds_read", "ds_bpermute", "ds_permute")) and q:
+                # a register the program overwrites is no longer one a pending read is awaited
+                # in: the compiler only reuses a register whose previous value is dead, and the
+                # kernels issue no read whose result is never used (without this, reads that are
+                # pending only on a path no execution takes -- requested at a hand-over, then
+                # loop exit -- would taint whatever the epilogue keeps in those registers)
+                q = [e if e == "smem" else e - ins.dst for e in q]
             if _is_lgkm(ins.op):
                 if ins.op.startswith("s_"):
                     q.append("smem")

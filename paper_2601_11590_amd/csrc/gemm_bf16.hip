@@ -85,6 +85,11 @@ template <int G> __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
+// LDS beyond the operand stages: the rotary epilogue keeps the tile's cos / sin table there, up
+// to 256 + QKV_TABLE_EXTRA bytes per token (head_dim 72 has 36 pairs of 8 bytes)
+constexpr int QKV_TABLE_EXTRA = 32;
+template <class T, int EPI> __host__ __device__ constexpr int lds_extra() { return EPI == 3 ? T::BM * QKV_TABLE_EXTRA : 0; }
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
@@ -225,7 +230,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   // per-segment sums the producing GEMM left.  Computed first, so that the loads complete in
   // the shadow of the main loop, and kept in LDS behind the stages and the staging area (the
   // barriers of the main loop make it visible to the epilogue).
-  float* const row_scale = (float*)(lds + T::LDS_BYTES);
+  float* const row_scale = (float*)(lds + T::LDS_BYTES + lds_extra<T, EPI>());
   const bool scaled = g.stats_in != nullptr;
   // eight segments (hidden 1024): the loads are issued here, ahead of the first operand
   // loads, and only consumed after the first barrier
@@ -245,6 +250,23 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       row_scale[r] = 1.0f / sqrtf(fmaf(ss, g.stats_inv_dim, g.stats_eps));
     }
   }
+
+  // bf16 store / activation epilogue: its bias values (4 columns per 8-column group of the
+  // lane) are fetched here, so that their latency passes in the shadow of the main loop; the
+  // largest tile has no registers to spare for them and fetches them in the epilogue
+  constexpr bool BF16_EPI = (EPI == EPI_STORE || EPI == EPI_GELU) && OUT == OUT_BF16 && !VMODE;
+  constexpr bool BIAS_PRE = BF16_EPI && BM * BN <= 256 * 256;
+  [[maybe_unused]] uint2 bb[TN][4];
+  auto load_bias = [&]() {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nb = n0 + wn * WN + j * 32 + q * 8 + lg * 4;
+        bb[j][q] = (g.bias && nb < g.N) ? *(const uint2*)((const uint16_t*)g.bias + nb) : make_uint2(0u, 0u);   // N is a multiple of 4
+      }
+  };
+  if constexpr (BIAS_PRE) load_bias();
 
   const int nk = (g.K + BK - 1) / BK;
   const bool ragged_k = (g.K % BK) != 0;
@@ -467,66 +489,50 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   } else if constexpr ((EPI == EPI_STORE || EPI == EPI_GELU) && OUT == OUT_BF16) {
     // bf16 output with a per-element epilogue that needs nothing but the element and its
     // column: scale, bias and activation are applied in the MFMA layout (a lane holds 4
-    // consecutive columns of one token) and the finished bf16 values are staged through LDS,
-    // the whole tile at once where it fits and in two column halves where not, to leave as
-    // 16-byte row-contiguous stores.  Half the LDS traffic of the fp32 staging below, all waves
-    // write at the same time, one or two passes instead of two or four.  (The rotary epilogue
-    // stays on the fp32 path: its cos / sin table is read row by row there; read from the MFMA
-    // layout, 32 rows per load instruction, it measured 25 % slower.)
-    constexpr int NP = BM * (BN * 2 + 16) <= T::LDS_BYTES ? 1 : 2;   // passes
-    constexpr int CP = BN / NP;                                      // columns per pass
-    constexpr int ROWO = CP * 2 + 16;                  // padded: 16 consecutive rows hit 16 different bank groups
-    static_assert(BM * ROWO <= T::LDS_BYTES && CP % WN == 0, "bf16 staging area");
-    constexpr int CPRO = CP / 8, RPSO = NT / CPRO;     // 16-byte chunks per row, rows per sweep
-    static_assert(BM % RPSO == 0, "sweeps");
-    float rsv[TM];
-#pragma unroll
-    for (int i = 0; i < TM; ++i) rsv[i] = 1.0f;
+    // consecutive columns of one token) and the finished bf16 values are staged through LDS to
+    // leave as 16-byte pieces of whole rows.  The passes split the tile by rows: pass i takes
+    // row block i of every wave (32 rows per wave row, all BN columns), so every wave -- every
+    // SIMD -- does a share of the activation arithmetic in every pass, and a row leaves as
+    // BN * 2 contiguous bytes.  Two staging buffers alternate, which leaves one barrier per
+    // pass: a buffer is rewritten two passes later, behind the barrier of the pass between.
+    constexpr int SR = T::WAVES_M * 32;                // rows per pass
+    constexpr int ROWO = BN * 2 + 16;                  // padded: 16 consecutive rows hit 16 different bank groups
+    constexpr int BUF = SR * ROWO;
+    constexpr int CPRO = BN / 8, RPSO = NT / CPRO;     // 16-byte chunks per row, rows per sweep
+    static_assert(2 * BUF <= T::LDS_BYTES && SR % RPSO == 0 && NT % CPRO == 0, "bf16 staging area");
     uint16_t* const outp = (uint16_t*)g.out;
     const int c8 = (tid % CPRO) * 8;
+    const int n = n0 + c8;
+    const bool vec = (g.ldo % 8 == 0) && (((size_t)outp & 15) == 0) && n + 8 <= g.N;
+    if constexpr (!BIAS_PRE) load_bias();
+    __syncthreads();                                   // the operand stages are dead from here on
 #pragma unroll
-    for (int ps = 0; ps < NP; ++ps) {
-      __syncthreads();
-      if (ps == 0 && scaled) {
+    for (int i = 0; i < TM; ++i) {
+      char* const buf = lds + (i & 1) * BUF;
+      const float rs = scaled ? row_scale[wm * WM + i * 32 + l32] : 1.0f;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) rsv[i] = row_scale[wm * WM + i * 32 + l32];
-      }
-      if ((wn * WN) / CP == ps) {
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int nl = wn * WN + j * 32 + q * 8 + lg * 4;      // column inside the tile
-            const int n = n0 + nl;
-            float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
-            if (bias && n < g.N) {                       // N is a multiple of 4: all or nothing
-              const uint2 bb = *(const uint2*)(bias + n);
-              b0 = bf16_bits_to_float(bb.x & 0xffff); b1 = bf16_bits_to_float(bb.x >> 16);
-              b2 = bf16_bits_to_float(bb.y & 0xffff); b3 = bf16_bits_to_float(bb.y >> 16);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-              const int ml = wm * WM + i * 32 + l32;
-              float v0 = fmaf(acc[i][j][4 * q], rsv[i], b0), v1 = fmaf(acc[i][j][4 * q + 1], rsv[i], b1);
-              float v2 = fmaf(acc[i][j][4 * q + 2], rsv[i], b2), v3 = fmaf(acc[i][j][4 * q + 3], rsv[i], b3);
-              if constexpr (EPI == EPI_GELU) {
-                if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
-                else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
-              }
-              *(uint2*)(lds + ml * ROWO + (nl - ps * CP) * 2) = pack_bf16x4(v0, v1, v2, v3);
-            }
+        for (int q = 0; q < 4; ++q) {
+          const int nl = wn * WN + j * 32 + q * 8 + lg * 4;        // column inside the tile
+          const float b0 = bf16_bits_to_float(bb[j][q].x & 0xffff), b1 = bf16_bits_to_float(bb[j][q].x >> 16);
+          const float b2 = bf16_bits_to_float(bb[j][q].y & 0xffff), b3 = bf16_bits_to_float(bb[j][q].y >> 16);
+          float v0 = fmaf(acc[i][j][4 * q], rs, b0), v1 = fmaf(acc[i][j][4 * q + 1], rs, b1);
+          float v2 = fmaf(acc[i][j][4 * q + 2], rs, b2), v3 = fmaf(acc[i][j][4 * q + 3], rs, b3);
+          if constexpr (EPI == EPI_GELU) {
+            if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
+            else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
           }
-      }
+          *(uint2*)(buf + (wm * 32 + l32) * ROWO + nl * 2) = pack_bf16x4(v0, v1, v2, v3);
+        }
       __syncthreads();
-      const int n = n0 + ps * CP + c8;
-      const bool vec = (g.ldo % 8 == 0) && (((size_t)outp & 15) == 0) && n + 8 <= g.N;
       if (n < g.N) {
 #pragma unroll
-        for (int sw = 0; sw < BM / RPSO; ++sw) {
+        for (int sw = 0; sw < SR / RPSO; ++sw) {
           const int r = sw * RPSO + tid / CPRO;
-          const int m = m0 + r;
+          const int m = m0 + (r / 32) * WM + i * 32 + (r % 32);
           if (m >= g.M) continue;
-          const uint4 v = *(const uint4*)(lds + r * ROWO + c8 * 2);
+          const uint4 v = *(const uint4*)(buf + r * ROWO + c8 * 2);
           uint16_t* dst = outp + (size_t)m * g.ldo + n;
           if (vec) {
             *(uint4*)dst = v;
@@ -534,6 +540,81 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
             for (int t = 0; t < 8 && n + t < g.N; ++t) dst[t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
           }
+        }
+      }
+    }
+  } else if constexpr (EPI == EPI_QKV) {
+    // Q | K columns with rotary: the passes split the tile by rows, not by columns.  Pass i
+    // stages row block i of every wave (32 rows per wave row, all BN columns, fp32), so all
+    // waves write at once and a wave then reads and stores whole rows (BN * 2 bytes contiguous
+    // in memory).  The cos / sin entries of the tile's tokens are one contiguous slab of the
+    // table; it is copied into LDS behind the staging area by direct-to-LDS loads issued before
+    // the first pass is staged, and every pass reads its entries from there (fetched from
+    // memory per pass, their latency was more than half of this epilogue).  Staging rows are
+    // unpadded and swizzled instead, 16-byte chunk c of row r at chunk c ^ (r % 16): staging
+    // plus a table of up to 256 + QKV_TABLE_EXTRA bytes per token then fill the operand stages
+    // exactly.  Larger tables (head_dim > 72) are read from memory.
+    constexpr int SR = T::WAVES_M * 32;                // rows per pass
+    constexpr int ROWE = BN * 4;
+    constexpr int STG = SR * ROWE;
+    constexpr int LPR4 = BN / 4, RPS = NT / LPR4;      // lanes per row (4 columns each), rows per sweep
+    static_assert(STG <= T::LDS_BYTES && SR % RPS == 0 && NT % LPR4 == 0 && LPR4 >= 16, "row-split staging");
+    const int cl = (tid % LPR4) * 4;
+    const int n = n0 + cl;                             // N is a multiple of 4: all or nothing
+    float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+    if (bias && n < g.N) {
+      const uint2 bb = *(const uint2*)(bias + n);
+      b0 = bf16_bits_to_float(bb.x & 0xffff); b1 = bf16_bits_to_float(bb.x >> 16);
+      b2 = bf16_bits_to_float(bb.y & 0xffff); b3 = bf16_bits_to_float(bb.y >> 16);
+    }
+    const int pr = (n % g.head_dim) >> 1;              // even: two pairs = one 16-byte entry
+    const int trb = g.rot_pairs * 8;                   // table bytes per token
+    const bool tab_lds = g.rot != nullptr && STG + BM * trb <= T::LDS_BYTES + lds_extra<T, EPI>();
+    const char* const tab = lds + STG;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      __syncthreads();
+      if (i == 0 && tab_lds) {
+        // BM * trb bytes from row m0 of the table, 16 bytes per lane, a wave fills 1 KB of LDS
+        // per instruction; rows past M are never used: their chunks re-read the last valid one
+        const char* src = (const char*)g.rot + (size_t)m0 * trb;
+        const long last = (long)(g.M - m0) * trb - 16;
+        for (int c0 = wave * 64; c0 < BM * (trb / 16); c0 += NT)
+          __builtin_amdgcn_global_load_lds(EPD_GPTR(src + min((long)(c0 + lane) * 16, last)), EPD_LPTR(tab + c0 * 16), 16, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int sr = wm * 32 + l32;
+          const int ch = (wn * WN + j * 32 + q * 8) / 4 + lg;
+          *(float4*)(lds + sr * ROWE + (ch ^ (sr & 15)) * 16) =
+              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+      if (i == 0) wait_vmcnt<0>();
+      __syncthreads();
+      if (n < g.N) {
+        // fully unrolled so that the LDS reads of all sweeps are in flight together
+#pragma unroll
+        for (int sw = 0; sw < SR / RPS; ++sw) {
+          const int r = sw * RPS + tid / LPR4;
+          const int ml = (r / 32) * WM + i * 32 + (r % 32);
+          const int m = m0 + ml;
+          if (m >= g.M) continue;
+          const float4 e = *(const float4*)(lds + r * ROWE + (((tid % LPR4) ^ (r & 15)) * 16));
+          const float rs = scaled ? row_scale[ml] : 1.0f;
+          float v0 = fmaf(e.x, rs, b0), v1 = fmaf(e.y, rs, b1), v2 = fmaf(e.z, rs, b2), v3 = fmaf(e.w, rs, b3);
+          if (g.rot) {
+            const float4 cs = tab_lds ? *(const float4*)(tab + ml * trb + pr * 8)
+                                      : *(const float4*)(g.rot + (size_t)m * g.rot_pairs + pr);
+            const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
+            const float r2 = v2 * cs.z - v3 * cs.w, r3 = v2 * cs.w + v3 * cs.z;
+            v0 = r0; v1 = r1; v2 = r2; v3 = r3;
+          }
+          // the softmax scale (in log2 units) rides on Q: one rounding of q * scale instead of
+          // a multiply per score in the attention kernel
+          if (n < g.q_cols) { v0 *= g.q_scale; v1 *= g.q_scale; v2 *= g.q_scale; v3 *= g.q_scale; }
+          *(uint2*)((uint16_t*)g.out + (size_t)m * g.ldo + n) = pack_bf16x4(v0, v1, v2, v3);
         }
       }
     }
@@ -570,8 +651,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         b0 = bf16_bits_to_float(bb.x & 0xffff); b1 = bf16_bits_to_float(bb.x >> 16);
         b2 = bf16_bits_to_float(bb.y & 0xffff); b3 = bf16_bits_to_float(bb.y >> 16);
       }
-      int pr = 0;
-      if constexpr (EPI == EPI_QKV) pr = (n % g.head_dim) >> 1;   // even: two pairs = one 16-byte entry
       // fully unrolled so that the residual loads / LDS reads of all sweeps are in flight together
 #pragma unroll
       for (int sw = 0; sw < BM / RPS; ++sw) {
@@ -581,17 +660,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         const float4 e = *(const float4*)(lds + r * ROWE + cl * 4);
         const float rs = scaled ? row_scale[r] : 1.0f;
         float v0 = fmaf(e.x, rs, b0), v1 = fmaf(e.y, rs, b1), v2 = fmaf(e.z, rs, b2), v3 = fmaf(e.w, rs, b3);
-        if constexpr (EPI == EPI_QKV) {
-          if (g.rot) {
-            const float4 cs = *(const float4*)(g.rot + (size_t)m * g.rot_pairs + pr);
-            const float r0 = v0 * cs.x - v1 * cs.y, r1 = v0 * cs.y + v1 * cs.x;
-            const float r2 = v2 * cs.z - v3 * cs.w, r3 = v2 * cs.w + v3 * cs.z;
-            v0 = r0; v1 = r1; v2 = r2; v3 = r3;
-          }
-          // the softmax scale (in log2 units) rides on Q: one rounding of q * scale instead of
-          // a multiply per score in the attention kernel
-          if (n < g.q_cols) { v0 *= g.q_scale; v1 *= g.q_scale; v2 *= g.q_scale; v3 *= g.q_scale; }
-        }
         if constexpr (EPI == EPI_GELU) {
           if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
           else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
@@ -654,7 +722,8 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
 
 template <class T, int EPI, int OUT, bool GATHER, bool FAST>
 __global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g) {
-  __shared__ __attribute__((aligned(1024))) char lds[T::LDS_BYTES + T::BM * 4];   // + per-row scales of the epilogue
+  // + room for a wider rotary table (QKV epilogue) + per-row scales of the epilogue
+  __shared__ __attribute__((aligned(1024))) char lds[T::LDS_BYTES + lds_extra<T, EPI>() + T::BM * 4];
   const int tiles_n = (g.N + T::BN - 1) / T::BN, tiles_m = (g.M + T::BM - 1) / T::BM;
   int tm, tn;
   tile_coords(xcd_remap(blockIdx.x, gridDim.x), tiles_m, tiles_n, g.group_m, tm, tn);

@@ -45,3 +45,12 @@ def test_pending_reads_are_followed_around_a_loop_and_across_a_branch():
 
 def test_a_file_without_the_kernel_is_an_error():
     assert C.check_asm("\t.text\n", ("gemm_bf16_kernel",)) != []
+
+
+def test_an_overwritten_register_is_no_longer_awaited():
+    # the read is pending only on the path that skips the wait; the register then gets a new
+    # value (an accumulator read back), and copying THAT is not a hazard
+    body = ("\tds_read_b128 v[4:7], v1\n\ts_cbranch_scc1 .LBB0_2\n\ts_waitcnt lgkmcnt(0)\n.LBB0_2:\n"
+            "\tv_accvgpr_read_b32 v4, a3\n\tv_mov_b32_e32 v20, v4\n\tv_mov_b32_e32 v21, v5\n")
+    e = errs(body)
+    assert len(e) == 1 and "v5" in e[0]                        # v5 was not overwritten: still flagged
