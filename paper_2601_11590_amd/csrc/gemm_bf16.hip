@@ -200,6 +200,17 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     char* const sw = lds + 2 * A_BYTES + stage * W_BYTES;
     const char* ab = a_base_ptr + (size_t)k0 * 2;
     const char* wb = w_base_ptr + (size_t)k0 * 2;
+    // The per-lane offsets pass through an opaque copy here, so that their widening to 64 bits
+    // stays next to the load: "scalar base + 32-bit lane offset" is then the load's own
+    // addressing form.  Widened once ahead of the loop, every offset would occupy a register
+    // pair for the whole loop and every load would need a 64-bit vector add in front of it.
+    // (one copy per load: a shared one would let the adds be re-associated into a running
+    // 64-bit vector address again)
+    uint32_t ao[LA], wo[LW];
+#pragma unroll
+    for (int it = 0; it < LA; ++it) { ao[it] = a_off[FAST ? 0 : it]; asm volatile("" : "+v"(ao[it])); }
+#pragma unroll
+    for (int it = 0; it < LW; ++it) { wo[it] = w_off[FAST ? 0 : it]; asm volatile("" : "+v"(wo[it])); }
 #pragma unroll
     for (int it = 0; it < LA; ++it) {
       const char* p;
@@ -210,9 +221,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
         const int src = g.gather[(size_t)(m0 + row) * g.gather_n + piece];
         p = (const char*)g.A + ((size_t)src * g.lda + (k - piece * kcw)) * 2;
       } else if constexpr (FAST) {
-        p = ab + (size_t)(it * RPP) * (size_t)g.lda * 2 + a_off[0];
+        p = (ab + (size_t)(it * RPP) * (size_t)g.lda * 2) + (size_t)ao[it];
       } else {
-        p = ab + a_off[it];
+        p = ab + (size_t)ao[it];
       }
       if constexpr (tail) { if (k0 + chunk_k(it) >= g.K) p = zeros; }
       __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(sa + (it * NT + wave * 64) * 16), 16, 0, 0);
@@ -220,8 +231,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
 #pragma unroll
     for (int it = 0; it < LW; ++it) {
       const char* p;
-      if constexpr (FAST) p = wb + (size_t)(it * RPP) * (size_t)ldw * 2 + w_off[0];
-      else p = wb + w_off[it];
+      if constexpr (FAST) p = (wb + (size_t)(it * RPP) * (size_t)ldw * 2) + (size_t)wo[it];
+      else p = wb + (size_t)wo[it];
       if constexpr (tail) { if (k0 + chunk_k(it) >= g.K) p = zeros; }
       __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(sw + (it * NT + wave * 64) * 16), 16, 0, 0);
     }
@@ -437,52 +448,62 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   const uint16_t* bias = (const uint16_t*)g.bias;
   wait_vmcnt<0>();
   if constexpr (VMODE) {
-    // staged transposed: ET[channel][token], so that a lane ends up with consecutive tokens
-    constexpr int ROWE = BM * 4 + 16;
+    // The MFMA operands are swapped for these tiles, so a lane holds 4 consecutive tokens of
+    // one channel: scale and bias are applied there and the bf16 values staged transposed,
+    // ET[channel][token], the whole tile at once where it fits and in two channel halves where
+    // not; a lane then takes 8 consecutive tokens (one 16-byte store) of a channel row.
+    constexpr int ROWV = BM * 2 + 16;
+    constexpr int NPV = BN * ROWV <= T::LDS_BYTES ? 1 : 2;          // passes
+    constexpr int CPV = BN / NPV;                                   // channels per pass
+    static_assert(CPV * ROWV <= T::LDS_BYTES && CPV % WN == 0, "transposed staging area");
     uint16_t* vt = (uint16_t*)g.vt;
+    // thread coordinates derived afresh (through an opaque copy of the thread id): nothing of
+    // this epilogue's index arithmetic is then computed ahead of the main loop and kept in
+    // registers across it, where the largest tile has none to spare
+    int tid_v = threadIdx.x;
+    asm volatile("" : "+v"(tid_v));
+    const int tid = tid_v, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N, l32 = lane & 31, lg = lane >> 5;
+    // BM tokens per channel row: BM/8 lanes per row, 8 tokens per lane
+    constexpr int LPRV = BM / 8, RPS = NT / LPRV;        // threads beyond RPS whole rows idle
+    const int tl = (tid % LPRV) * 8;
+    const int m = tid < RPS * LPRV ? m0 + tl : g.M;
+    int4 vc0 = make_int4(0, 0, 0, 0), vc1 = make_int4(0, 0, 0, 0);
+    const bool full = m + 7 < g.M;
+    if (full) { vc0 = *(const int4*)(g.vcol + m); vc1 = *(const int4*)(g.vcol + m + 4); }
+    const bool fast = full && (vc1.w - vc0.x == 7) && ((vc0.x & 7) == 0);
 #pragma unroll
-    for (int h = 0; h < NPASS; ++h) {
+    for (int ps = 0; ps < NPV; ++ps) {
       __syncthreads();
-      if (wn / WPH == h) {
+      if ((wn * WN) / CPV == ps) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          const int ch = (wn % WPH) * WN + j * 32 + l32;
+          const int chl = wn * WN + j * 32 + l32;        // channel inside the tile
+          const float bv = (bias && n0 + chl < g.N) ? bf16_bits_to_float(bias[n0 + chl]) : 0.f;
 #pragma unroll
           for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               const int ml = wm * WM + i * 32 + q * 8 + lg * 4;
-              *(float4*)(lds + ch * ROWE + ml * 4) =
-                  make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+              float4 rs = make_float4(1.f, 1.f, 1.f, 1.f);
+              if (scaled) rs = *(const float4*)(row_scale + ml);
+              *(uint2*)(lds + (chl - ps * CPV) * ROWV + ml * 2) =
+                  pack_bf16x4(fmaf(acc[i][j][4 * q], rs.x, bv), fmaf(acc[i][j][4 * q + 1], rs.y, bv),
+                              fmaf(acc[i][j][4 * q + 2], rs.z, bv), fmaf(acc[i][j][4 * q + 3], rs.w, bv));
             }
         }
       }
       __syncthreads();
-      // BM tokens per channel row: BM/8 lanes per row, 8 tokens (one 16-byte bf16 store) per lane
-      constexpr int LPRV = BM / 8, RPS = NT / LPRV;      // threads beyond RPS whole rows idle
-      const int tl = (tid % LPRV) * 8;
-      const int m = tid < RPS * LPRV ? m0 + tl : g.M;
-      int4 vc0 = make_int4(0, 0, 0, 0), vc1 = make_int4(0, 0, 0, 0);
-      const bool full = m + 7 < g.M;
-      if (full) { vc0 = *(const int4*)(g.vcol + m); vc1 = *(const int4*)(g.vcol + m + 4); }
-      const bool fast = full && (vc1.w - vc0.x == 7) && ((vc0.x & 7) == 0);
-      float4 rs0 = make_float4(1.f, 1.f, 1.f, 1.f), rs1 = rs0;
-      if (scaled) { rs0 = *(const float4*)(row_scale + tl); rs1 = *(const float4*)(row_scale + tl + 4); }
-      for (int r = tid / LPRV; r < HALF; r += RPS) {
-        const int n = n0 + h * HALF + r;
+      for (int r = tid / LPRV; r < CPV; r += RPS) {
+        const int n = n0 + ps * CPV + r;
         if (n >= g.N || m >= g.M) continue;
-        const float bv = bias ? bf16_bits_to_float(bias[n]) : 0.f;
-        const float4 e0 = *(const float4*)(lds + r * ROWE + tl * 4);
-        const float4 e1 = *(const float4*)(lds + r * ROWE + tl * 4 + 16);
-        const uint2 p0 = pack_bf16x4(fmaf(e0.x, rs0.x, bv), fmaf(e0.y, rs0.y, bv), fmaf(e0.z, rs0.z, bv), fmaf(e0.w, rs0.w, bv));
-        const uint2 p1 = pack_bf16x4(fmaf(e1.x, rs1.x, bv), fmaf(e1.y, rs1.y, bv), fmaf(e1.z, rs1.z, bv), fmaf(e1.w, rs1.w, bv));
+        const uint4 p = *(const uint4*)(lds + r * ROWV + tl * 2);
         uint16_t* vrow = vt + (size_t)(n - g.qk_cols) * g.vt_stride;
         if (fast) {
-          *(uint4*)(vrow + vc0.x) = make_uint4(p0.x, p0.y, p1.x, p1.y);
+          *(uint4*)(vrow + vc0.x) = p;
         } else {
-          const uint16_t e[8] = {(uint16_t)(p0.x & 0xffff), (uint16_t)(p0.x >> 16), (uint16_t)(p0.y & 0xffff), (uint16_t)(p0.y >> 16),
-                                 (uint16_t)(p1.x & 0xffff), (uint16_t)(p1.x >> 16), (uint16_t)(p1.y & 0xffff), (uint16_t)(p1.y >> 16)};
-          for (int t = 0; t < 8 && m + t < g.M; ++t) vrow[g.vcol[m + t]] = e[t];
+          const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+          for (int t = 0; t < 8 && m + t < g.M; ++t) vrow[g.vcol[m + t]] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
         }
       }
     }
