@@ -104,7 +104,8 @@ typedef struct {
   int32_t final_norm;   /* 1: norm before the merger                                           */
   int32_t merge;        /* spatial merge size m (2; 1 = no gather)                             */
   int32_t out_dim;      /* width of V_m                                                        */
-  int32_t max_tokens;   /* largest T (packed patch rows) of any call                           */
+  int32_t max_tokens;   /* largest T (packed patch rows) of any call; bf16: max_tokens *
+                           hidden < 2^30 (EPD_ERR_UNSUPPORTED beyond)                          */
   int32_t max_segments; /* largest number of attention segments of any call                    */
   int32_t max_items;    /* largest number of images / clips of any call                        */
   const epd_weights* weights; /* HOST struct of device pointers; read (copied into the

@@ -160,15 +160,20 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     for (int it = 0; it < LK; ++it) {
       if (k_on[it]) {
         const int r = min(kv0 + k_row[it], w.seg_len - 1);   // rows past the segment repeat its last key (masked later)
-        const char* p = kbase + (size_t)r * a.ld_qkv * 2 + k_ch[it] * 16;
-        __builtin_amdgcn_global_load_lds(EPD_GPTR(p), EPD_LPTR(sb + (it * 256 + wave * 64) * 16), 16, 0, 0);
+        // scalar base + 32-bit lane offset: the load's own addressing form, no 64-bit vector
+        // arithmetic (a segment's K rows span far less than 4 GB)
+        const uint32_t off = (uint32_t)r * (uint32_t)(a.ld_qkv * 2) + (uint32_t)(k_ch[it] * 16);
+        __builtin_amdgcn_global_load_lds(EPD_GPTR(kbase + (size_t)off), EPD_LPTR(sb + (it * 256 + wave * 64) * 16), 16, 0, 0);
       }
     }
     const char* vb = vbase + (size_t)kv0 * 2;
 #pragma unroll
     for (int it = 0; it < LV; ++it) {
-      if (v_on[it])
-        __builtin_amdgcn_global_load_lds(EPD_GPTR(vb + v_off[it]), EPD_LPTR(sb + KBYTES + (it * 256 + wave * 64) * 16), 16, 0, 0);
+      if (v_on[it]) {
+        uint32_t off = v_off[it];
+        asm volatile("" : "+v"(off));        // keeps the widening to 64 bits next to the load (same form as above)
+        __builtin_amdgcn_global_load_lds(EPD_GPTR(vb + (size_t)off), EPD_LPTR(sb + KBYTES + (it * 256 + wave * 64) * 16), 16, 0, 0);
+      }
     }
   };
 

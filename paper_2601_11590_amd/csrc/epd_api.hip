@@ -182,6 +182,11 @@ epd_status validate_cfg(const epd_encode_cfg* c, bool need_buffers, std::string&
   if ((int64_t)c->max_tokens + (int64_t)c->max_segments * kVtAlign > (1ll << 30)) {
     err = "max_tokens too large"; return EPD_ERR_UNSUPPORTED;
   }
+  // the bf16 attention kernel addresses the K rows of a segment with 32-bit byte offsets
+  // (rows of 2 * hidden bf16 values)
+  if (c->dtype == EPD_BF16 && (int64_t)c->max_tokens * c->hidden * 4 >= (1ll << 32)) {
+    err = "max_tokens * hidden too large (bf16: must stay below 2^30)"; return EPD_ERR_UNSUPPORTED;
+  }
   if (!need_buffers) return EPD_OK;
   const epd_weights* w = c->weights;
   if (!w) { err = "cfg.weights is NULL"; return EPD_ERR_INVALID_ARG; }
