@@ -113,6 +113,13 @@ def test_create_rejects_bad_shapes_on_the_host(change, status, needle):
     assert needle in msg, msg
 
 
+def test_create_rejects_token_counts_beyond_the_32_bit_k_offsets_of_bf16_attention():
+    # rows of 2 * hidden bf16 values, addressed with 32-bit byte offsets inside a segment
+    st, msg = _create_error(TINY, max_tokens=(1 << 30) // 64)
+    assert st == B.EPD_ERR_UNSUPPORTED and "max_tokens * hidden" in msg, msg
+    assert B.epd_encode_workspace_bytes(B.make_cfg(TINY, (1 << 30) // 64 - 1, 4, 4)) > 0
+
+
 def test_create_rejects_bad_pointers_enums_and_workspace():
     st, msg = _create_error(TINY, lambda c: setattr(c, "struct_size", 12))
     assert st == B.EPD_ERR_INVALID_ARG and "struct_size" in msg
