@@ -129,7 +129,8 @@ struct Tile {
   static constexpr int CPR = BK / 8;                     // 16-byte chunks per tile row
   static constexpr int LA = BM * CPR / NT, LW = BN * CPR / NT;   // load instructions per thread and stage
   static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
-  // fp32 epilogue staging: the tile's columns in 2 passes, or 4 where two would not fit LDS
+  // fp32 epilogue staging (residual add, fp32 outputs): the tile's columns in 2 passes, or 4
+  // where two would not fit LDS
   static constexpr int EPI_PASSES = BM * (BN / 2 * 4 + 16) <= 136 * 1024 ? 2 : 4;
   static constexpr int EPI_BYTES_A = BM * (BN / EPI_PASSES * 4 + 16), EPI_BYTES_V = (BN / EPI_PASSES) * (BM * 4 + 16);
   static constexpr int LDS_BYTES = (2 * STAGE_BYTES > EPI_BYTES_A ? 2 * STAGE_BYTES : EPI_BYTES_A) > EPI_BYTES_V
@@ -437,10 +438,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   // ------------------------------------------------------------------ epilogue
   // The accumulators go through LDS (the operand stages are dead by now) so that global
   // memory sees row-contiguous accesses: straight from the MFMA layout every store
-  // instruction would touch 32 different rows with 16 bytes each.  Two passes, each staging
-  // one half of the tile's columns as fp32 (BM rows x BN/2 floats, rows padded by 16 bytes);
-  // then every group of 32 lanes owns one row and a lane owns 4 consecutive columns, which is
-  // where bias, activation, rotary and the residual add are applied.
+  // instruction would touch 32 different rows with 16 bytes each.  Four forms follow: the V
+  // tiles of QKV (transposed), bf16 store / activation and Q | K with rotary (passes over row
+  // blocks, described where they stand), and the general one, used by the residual add and
+  // fp32 outputs: two or four passes, each staging a slice of the tile's columns as fp32 (BM
+  // rows x BN/passes floats, rows padded by 16 bytes); then every group of 16 or 32 lanes owns
+  // one row and a lane owns 4 consecutive columns, which is where bias and the residual add
+  // are applied.
   constexpr int NPASS = T::EPI_PASSES;
   constexpr int HALF = BN / NPASS;                    // columns per pass
   constexpr int WPH = T::WAVES_N / NPASS;             // wave columns per pass
