@@ -17,8 +17,9 @@ youngest N (scalar loads may complete out of order: each one in the queue is ass
 taken one of the completions the wait guarantees).  Where paths with different queues meet they
 are aligned at the youngest entry and united position by position.  Queues are cut to the 16
 operations the hardware counter can hold.  A register that a later instruction overwrites leaves
-the pending sets: what is checked is a copy of a value that has not arrived, not the reuse of a
-register.
+the pending sets (reads pending only on paths no execution takes must not taint the registers'
+next values) -- except where the read was issued in the same basic block: that overwrite is on a
+real path, the LDS return would clobber the new value, and it is reported.
 """
 
 from __future__ import annotations
@@ -153,6 +154,7 @@ def check_function(name: str, first_line: int, body: List[str]) -> List[str]:
     while work:
         bi = work.pop()
         q = list(state_in[bi])
+        local = 0            # the youngest `local` entries of q were issued in this very block
         for ins in blocks[bi]["insts"]:
             pending = frozenset().union(*[e for e in q if e != "smem"]) if q else frozenset()
             touched = ins.src & pending if ins.op.startswith(_COPY_OPS) else frozenset()
@@ -177,18 +179,30 @@ def check_function(name: str, first_line: int, body: List[str]) -> List[str]:
                         else:
                             kept.append(e)
                     q = kept
+                local = min(local, len(q))
+            if ins.dst and local and not ins.op.startswith(("ds_read", "ds_bpermute", "ds_permute")):
+                # an overwrite of a register whose read was issued in this same block and is
+                # still pending is on a path that is certainly taken: the LDS return would land
+                # on top of the new value
+                mine = frozenset().union(*[e for e in q[len(q) - local:] if e != "smem"])
+                hit = ins.dst & mine
+                if hit and (ins.line, "w") not in seen_err:
+                    seen_err.add((ins.line, "w"))
+                    regs = ", ".join("%s%d" % r for r in sorted(hit)[:6])
+                    errors.append("%s: asm line %d: `%s` overwrites %s while an LDS read into it is in flight"
+                                  % (name, ins.line, ins.text, regs))
             if ins.dst and not ins.op.startswith(("ds_read", "ds_bpermute", "ds_permute")) and q:
-                # a register the program overwrites is no longer one a pending read is awaited
-                # in: the compiler only reuses a register whose previous value is dead, and the
-                # kernels issue no read whose result is never used (without this, reads that are
-                # pending only on a path no execution takes -- requested at a hand-over, then
-                # loop exit -- would taint whatever the epilogue keeps in those registers)
+                # otherwise a register the program overwrites is no longer one a pending read is
+                # awaited in (without this, reads that are pending only on a path no execution
+                # takes -- requested at a hand-over, then loop exit -- would taint whatever the
+                # epilogue keeps in those registers)
                 q = [e if e == "smem" else e - ins.dst for e in q]
             if _is_lgkm(ins.op):
                 if ins.op.startswith("s_"):
                     q.append("smem")
                 else:
                     q.append(ins.dst if ins.op.startswith(("ds_read", "ds_bpermute", "ds_permute")) else frozenset())
+                local = min(local + 1, _MAX_OUTSTANDING)
         out: Entry = tuple(q[-_MAX_OUTSTANDING:])
         for s in blocks[bi]["succ"]:
             new = merge(state_in[s], out) if s in state_in else out

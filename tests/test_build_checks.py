@@ -40,7 +40,7 @@ def test_pending_reads_are_followed_around_a_loop_and_across_a_branch():
     assert len(errs(branch)) == 1
     # spills count as copies; ordinary arithmetic on the path-insensitive walk does not
     assert len(errs("\tds_read_b128 v[4:7], v1\n\tscratch_store_dword off, v4, off\n\ts_waitcnt lgkmcnt(0)\n")) == 1
-    assert errs("\tds_read_b128 v[4:7], v1\n\tv_add_u32_e32 v4, v2, v3\n\ts_waitcnt lgkmcnt(0)\n") == []
+    assert errs("\tds_read_b128 v[4:7], v1\n\tv_add_u32_e32 v20, v4, v3\n\ts_waitcnt lgkmcnt(0)\n") == []
 
 
 def test_a_file_without_the_kernel_is_an_error():
@@ -54,3 +54,16 @@ def test_an_overwritten_register_is_no_longer_awaited():
             "\tv_accvgpr_read_b32 v4, a3\n\tv_mov_b32_e32 v20, v4\n\tv_mov_b32_e32 v21, v5\n")
     e = errs(body)
     assert len(e) == 1 and "v5" in e[0]                        # v5 was not overwritten: still flagged
+
+
+def test_overwriting_a_register_with_a_read_in_flight_in_the_same_block_is_flagged():
+    bad = "\tds_read_b128 v[4:7], v1\n\tv_add_u32_e32 v5, v2, v3\n\ts_waitcnt lgkmcnt(0)\n"
+    e = errs(bad)
+    assert len(e) == 1 and "overwrites v5" in e[0]
+    good = "\tds_read_b128 v[4:7], v1\n\ts_waitcnt lgkmcnt(0)\n\tv_add_u32_e32 v5, v2, v3\n"
+    assert errs(good) == []
+    # counted wait: the older read has landed, the younger has not
+    two = ("\tds_read_b128 v[4:7], v1\n\tds_read_b128 v[8:11], v1\n\ts_waitcnt lgkmcnt(1)\n"
+           "\tv_mov_b32_e32 v4, v20\n\tv_mov_b32_e32 v9, v20\n")
+    e = errs(two)
+    assert len(e) == 1 and "overwrites v9" in e[0]
