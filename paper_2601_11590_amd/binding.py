@@ -56,7 +56,7 @@ class epd_encode_cfg(C.Structure):
 
 
 EXPORTS = ["epd_encode_workspace_bytes", "epd_encode_create", "epd_encode", "epd_encode_destroy",
-           "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing",
+           "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing", "epd_encode_set_tuning",
            "epd_encode_get_timing", "epd_preprocess", "epd_encode_cached", "epd_store_create",
            "epd_store_destroy", "epd_store_last_error", "epd_store_hash", "epd_store_lookup", "epd_store_insert",
            "epd_store_stats"]
@@ -100,6 +100,8 @@ def _load() -> C.CDLL:
     lib.epd_encode_debug_hidden.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.epd_encode_set_timing.restype = C.c_int
     lib.epd_encode_set_timing.argtypes = [C.c_void_p, C.c_int32]
+    lib.epd_encode_set_tuning.restype = C.c_int
+    lib.epd_encode_set_tuning.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.epd_encode_get_timing.restype = C.c_int
     lib.epd_encode_get_timing.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                           C.POINTER(C.c_double)]
@@ -259,6 +261,12 @@ def epd_encode_set_timing(handle, step: int) -> None:
         raise EpdError(st, epd_encode_last_error(handle))
 
 
+def epd_encode_set_tuning(handle, gemm_tile: int, attn_groups: int) -> None:
+    st = lib.epd_encode_set_tuning(handle, gemm_tile, attn_groups)
+    if st != EPD_OK:
+        raise EpdError(st, epd_encode_last_error(handle))
+
+
 def epd_encode_get_timing(handle):
     ms, n, work = C.c_double(), C.c_int64(), C.c_double()
     st = lib.epd_encode_get_timing(handle, C.byref(ms), C.byref(n), C.byref(work))
@@ -411,6 +419,9 @@ class EpdEncoder:
 
     def get_timing(self):
         return epd_encode_get_timing(self.handle)
+
+    def set_tuning(self, gemm_tile: int = -1, attn_groups: int = 0) -> None:
+        epd_encode_set_tuning(self.handle, gemm_tile, attn_groups)
 
     def close(self) -> None:
         if self.handle is not None:

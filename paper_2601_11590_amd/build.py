@@ -6,6 +6,7 @@ hipcc cross-compiles for gfx950 without a GPU being present.
 
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -14,6 +15,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libepd_encode.so")
+STAMP = LIB + ".hash"         # source_hash() of the sources LIB was built from
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["epd_api.hip", "plan_norm.hip", "preprocess.hip", "mm_store.hip", "kernels_f32.hip", "gemm_bf16.hip", "attn_bf16.hip"]
 
@@ -38,9 +40,35 @@ def _run(cmd):
     return r.stdout
 
 
+def source_hash(extra_flags=()) -> str:
+    """SHA-256 over everything the binary depends on: every file under csrc/, the public
+    header, the compiler flags and the source list."""
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC))
+    files.append(os.path.join(os.path.dirname(HERE), "include", "epd_encode.h"))
+    for path in files:
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+        h.update(b"\0")
+    h.update(repr((SOURCES, FLAGS, tuple(extra_flags))).encode())
+    return h.hexdigest()
+
+
+def built_hash() -> str:
+    """The hash stored next to the library when it was built ('' if there is none)."""
+    try:
+        with open(STAMP) as f:
+            return f.read().strip()
+    except OSError:
+        return ""
+
+
 def build(verbose: bool = False, extra_flags=()) -> str:
     """Compile every source and link the shared library.  Returns its path."""
     os.makedirs(OBJ_DIR, exist_ok=True)
+    if os.path.exists(STAMP):
+        os.remove(STAMP)
     hipcc = _hipcc()
     objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
 
@@ -61,14 +89,23 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     out = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose and out.strip():
         print(out)
+    with open(STAMP, "w") as f:
+        f.write(source_hash(extra_flags) + "\n")
     return LIB
 
 
 def library_path(build_if_missing: bool = True) -> str:
-    """Path of the built library; builds it once if nothing has been built yet."""
-    if not os.path.exists(LIB):
+    """Path of the built library.  The library is tied to its sources by the hash stored next
+    to it: a missing library, a missing stamp or a stamp that differs from the hash of the
+    sources as they stand (an edit without a rebuild) makes this build again, loudly, so that
+    tests and benchmarks never run a binary that is not the committed source."""
+    have = os.path.exists(LIB)
+    stale = have and built_hash() != source_hash()
+    if not have or stale:
         if not build_if_missing:
-            raise FileNotFoundError(LIB)
+            raise FileNotFoundError(LIB if not have else LIB + " is older than its sources")
+        print("[epd build] %s: building libepd_encode.so now (hipcc, about two minutes)"
+              % ("the library is STALE against csrc/" if stale else "no library yet"), file=sys.stderr, flush=True)
         build()
     return LIB
 

@@ -28,7 +28,6 @@
 // beyond d and never storing output rows beyond d.
 #include "epd_internal.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace epd {
@@ -435,23 +434,20 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
 // register): +6-10 % over three, and a batch of eight 784-token images x 16 heads (3200 wave
 // tasks) then fits the chip's 4096 wave slots in one round.
 static int bf16_nq(int head_dim, int max_seg_len) {
-  static int forced = [] {
-    const char* e = getenv("EPD_ATTN_NQ");
-    return e ? atoi(e) : 0;
-  }();
-  if (forced == 1 || forced == 2) return forced;
   return (head_dim <= 64 && max_seg_len > 1024) ? 2 : 1;
 }
 
-int attn_q_tile(bool bf16, int head_dim, int max_seg_len) {
+int attn_q_tile(bool bf16, int head_dim, int max_seg_len, int groups) {
   if (!bf16) {
     switch (head_dim) {
       case 8: case 16: case 32: case 64: case 72: case 80: case 96: case 128: return 64;
       default: return 0;
     }
   }
+  if (groups < 0 || groups > 2 || (groups == 2 && head_dim > 64)) return 0;
   switch (head_dim) {
-    case 32: case 64: case 72: case 80: case 96: case 128: return 128 * bf16_nq(head_dim, max_seg_len);
+    case 32: case 64: case 72: case 80: case 96: case 128:
+      return 128 * (groups ? groups : bf16_nq(head_dim, max_seg_len));
     default: return 0;
   }
 }
@@ -463,20 +459,23 @@ bool launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   // The row of ones is used where the head dim leaves spare rows in its last 32-row block of
   // O^T (d = 72, 80: +3 % measured); for d = 32, 64, 96, 128 it would add a block of matrix
   // instructions and measured 2-7 % slower.
-#define EPD_ATTN(DH, MB2)                                                                                \
+#define EPD_ATTN(DH)                                                                                     \
   case DH: {                                                                                             \
     constexpr bool sr = (DH % 32) != 0;                                                                  \
-    if (nq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, MB2, sr>), grid, block, 0, s, a);           \
-    else hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, (DH <= 64 ? 4 : 2), sr>), grid, block, 0, s, a);   \
+    if constexpr (DH <= 64) {                                                                            \
+      if (nq == 2) { hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, 2, sr>), grid, block, 0, s, a); return true; } \
+    }                                                                                                    \
+    if (nq != 1) return false;                                                                           \
+    hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, (DH <= 64 ? 4 : 2), sr>), grid, block, 0, s, a);        \
     return true;                                                                                         \
   }
   switch (a.head_dim) {
-    EPD_ATTN(32, 2);
-    EPD_ATTN(64, 2);
-    EPD_ATTN(72, 1);
-    EPD_ATTN(80, 1);
-    EPD_ATTN(96, 1);
-    EPD_ATTN(128, 1);
+    EPD_ATTN(32);
+    EPD_ATTN(64);
+    EPD_ATTN(72);
+    EPD_ATTN(80);
+    EPD_ATTN(96);
+    EPD_ATTN(128);
     default:
       return false;
   }

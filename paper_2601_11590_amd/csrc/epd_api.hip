@@ -187,6 +187,13 @@ epd_status validate_cfg(const epd_encode_cfg* c, bool need_buffers, std::string&
   if (c->dtype == EPD_BF16 && (int64_t)c->max_tokens * c->hidden * 4 >= (1ll << 32)) {
     err = "max_tokens * hidden too large (bf16: must stay below 2^30)"; return EPD_ERR_UNSUPPORTED;
   }
+  // ... and the rows of one head's transposed V tile the same way: head_dim rows of
+  // (max_tokens + 128 * max_segments) bf16 columns each
+  if (c->dtype == EPD_BF16 &&
+      (int64_t)c->head_dim * ((int64_t)c->max_tokens + (int64_t)c->max_segments * kVtAlign + kVtAlign) * 2 >= (1ll << 32)) {
+    err = "head_dim * (max_tokens + 128 * max_segments) too large (bf16: must stay below 2^31)";
+    return EPD_ERR_UNSUPPORTED;
+  }
   if (!need_buffers) return EPD_OK;
   const epd_weights* w = c->weights;
   if (!w) { err = "cfg.weights is NULL"; return EPD_ERR_INVALID_ARG; }
@@ -221,6 +228,9 @@ struct epd_encoder {
   int next_slot = 0;
   int last_T = 0;
   // timing
+  // tuning hook (epd_encode_set_tuning): 0 = the library's own choice
+  int tile_cfg = 0;      // k > 0: bf16 GEMM tile variant k - 1
+  int attn_groups = 0;   // 1 or 2: 32-row query groups per wave of the bf16 attention kernel
   int timed_step = -1;
   std::vector<hipEvent_t> ev;     // pairs (start, stop), created lazily
   int ev_used = 0;
@@ -440,7 +450,8 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
   // of the launch is made of short items
   int max_len = 0;
   for (int s = 0; s < S; ++s) max_len = std::max(max_len, cu[s + 1] - cu[s]);
-  const int bq = q_tile(c, max_len);
+  const int bq = attn_q_tile(bf, c.head_dim, max_len, h->attn_groups);
+  if (bq <= 0) { h->err = "internal: no attention kernel for the forced query tile"; return EPD_ERR_UNSUPPORTED; }
   std::vector<int> order(S);
   for (int s = 0; s < S; ++s) order[s] = s;
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cu[a + 1] - cu[a] > cu[b + 1] - cu[b]; });
@@ -490,6 +501,7 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
     g.zeros = h->ws + L.zeros;
     // operands that live in the workspace may be read past their last row (see make_layout)
     g.overread_ok = (g.A != packed_patches && !g.gather) ? 1 : 0;
+    g.tile_cfg = h->tile_cfg;
     if (bf) launch_gemm_bf16(g, st); else launch_gemm_f32(g, st);
   };
   auto norm = [&](const void* gma, const void* bta, void* dst) {
@@ -556,6 +568,7 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
       g.M = T; g.N = D; g.K = L.fpad;   // pad columns of Hd and of the weights are zero
       g.epilogue = EPI_RESIDUAL; g.resid = X; g.ldr = D;
       if (L.fold_rms && l + 1 < c.num_layers) produce_stats(g);
+      g.name_tag = 1;
       gemm(EPD_STEP_FC2, g, (int)F);
     }
   }
@@ -756,6 +769,20 @@ epd_status epd_encode_cached(epd_handle h, epd_store_handle s, uint64_t model_sa
       EPD_HIP(h, hipMemcpyAsync(slot, src, bytes, hipMemcpyDeviceToDevice, st));
     m0 += (size_t)(mrg[i + 1] - mrg[i]);
   }
+  return EPD_OK;
+}
+
+epd_status epd_encode_set_tuning(epd_handle h, int32_t gemm_tile, int32_t attn_groups) {
+  if (!h) { g_create_error = "handle is NULL"; return EPD_ERR_INVALID_ARG; }
+  if (gemm_tile != -1 && gemm_tile != 0 && gemm_tile != 2 && gemm_tile != 4 && gemm_tile != 5) {
+    h->err = fmt("gemm_tile %d: -1 (automatic), 0, 2, 4 or 5", gemm_tile); return EPD_ERR_INVALID_ARG;
+  }
+  if (attn_groups < 0 || attn_groups > 2) { h->err = fmt("attn_groups %d: 0 (automatic), 1 or 2", attn_groups); return EPD_ERR_INVALID_ARG; }
+  if (attn_groups && attn_q_tile(h->cfg.dtype == EPD_BF16, h->cfg.head_dim, 1, attn_groups) <= 0) {
+    h->err = fmt("attn_groups %d has no kernel for head_dim %d", attn_groups, h->cfg.head_dim); return EPD_ERR_UNSUPPORTED;
+  }
+  h->tile_cfg = gemm_tile + 1;
+  h->attn_groups = h->cfg.dtype == EPD_BF16 ? attn_groups : 0;
   return EPD_OK;
 }
 

@@ -62,7 +62,8 @@ struct GemmArgs {
   float stats_inv_dim, stats_eps;
   int tile_cfg;         // bf16 path: 0 = automatic choice, k > 0 = tile variant k - 1 (tuning)
   int group_m;          // bf16 path: row tiles per rasterisation group (set by the launcher)
-  unsigned long long* trace;  // tuning builds only (EPD_GEMM_TRACE): per-wave stall cycle counters
+  int name_tag;         // bf16 path, EPI_RESIDUAL: 1 = the second MLP GEMM (a kernel name of its own in
+                        //   profiles; the code is the same)
 };
 
 // ---------------------------------------------------------------- attention description
@@ -113,8 +114,10 @@ bool launch_attn_f32(const AttnArgs& a, hipStream_t s);   // false: head_dim not
 void launch_gemm_bf16(const GemmArgs& g, hipStream_t s);
 bool launch_attn_bf16(const AttnArgs& a, hipStream_t s);  // false: head_dim not covered
 // query rows per work item for segments up to max_seg_len (0 = unsupported head_dim);
-// never smaller than attn_q_tile(bf16, head_dim, 1)
-int attn_q_tile(bool bf16, int head_dim, int max_seg_len);
+// never smaller than attn_q_tile(bf16, head_dim, 1).  groups: 0 = the library's choice; 1 or 2 =
+// that many 32-row groups per wave on the bf16 path (2 exists for head_dim <= 64 only; 0 is
+// returned where the request has no kernel)
+int attn_q_tile(bool bf16, int head_dim, int max_seg_len, int groups = 0);
 // W[n][k] *= gamma[k] (bf16, in place): folds the scale of an RMSNorm into the weights of the
 // linear layer that consumes its output, so that  (x * rstd * gamma) W^T = rstd * (x (W gamma)^T)
 void launch_fold_gamma(void* w, const void* gamma, int N, int K, hipStream_t s);

@@ -25,7 +25,6 @@
 #include "epd_internal.h"
 
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 namespace epd {
@@ -365,10 +364,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   // barrier (everybody's loads landed, everybody finished reading stage s), refill stage s
   // with K step kt+2, start reading stage s^1 -- and only then issue the MFMAs of the last
   // slice, which cover the barrier and the LDS latency.  Every load has one full K step to land.
-#ifdef EPD_GEMM_TRACE
-  unsigned long long tr_vm = 0, tr_bar = 0;
-  const unsigned long long tr_start = __builtin_readcyclecounter();
-#endif
   issue_step(0, 0);
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
@@ -393,19 +388,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       } else {
         // last slice (fragment buffer 1): stage hand-over first
         if (kt + 1 < nk) {
-#ifdef EPD_GEMM_TRACE
-          wait_frags(I1{}, I0{});
-          const unsigned long long c0 = __builtin_readcyclecounter();
-          wait_vmcnt<0>();
-          const unsigned long long c1 = __builtin_readcyclecounter();
-          __builtin_amdgcn_s_barrier();
-          const unsigned long long c2 = __builtin_readcyclecounter();
-          tr_vm += c1 - c0; tr_bar += c2 - c1;
-#else
           wait_vmcnt<0>();
           wait_frags(I1{}, I0{});
           __builtin_amdgcn_s_barrier();
-#endif
           if constexpr (!LATE_REFILL) {
             if (kt + 2 < nk) issue_step(s, kt + 2);
           }
@@ -432,9 +417,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   }
   if (nk == 1) prefetch_resid();
 
-#ifdef EPD_GEMM_TRACE
-  const unsigned long long tr_loop_end = __builtin_readcyclecounter();
-#endif
   // ------------------------------------------------------------------ epilogue
   // The accumulators go through LDS (the operand stages are dead by now) so that global
   // memory sees row-contiguous accesses: straight from the MFMA layout every store
@@ -716,13 +698,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       }
     }
   }
-#ifdef EPD_GEMM_TRACE
-  if (g.trace && lane == 0) {
-    const unsigned long long tr_end = __builtin_readcyclecounter();
-    unsigned long long* t = g.trace + ((size_t)blockIdx.x * (NT / 64) + wave) * 4;
-    t[0] = tr_vm; t[1] = tr_bar; t[2] = tr_loop_end - tr_start; t[3] = tr_end - tr_loop_end;
-  }
-#endif
 }
 
 // Consecutive hardware block ids go to different XCDs (8 per chip, each with its own 4 MB
@@ -745,7 +720,9 @@ __device__ __forceinline__ void tile_coords(int t, int tiles_m, int tiles_n, int
   tm = first + (local - tn * rows);
 }
 
-template <class T, int EPI, int OUT, bool GATHER, bool FAST>
+// TAG changes nothing in the code: it gives the two residual GEMMs of a block (attention output
+// projection, second MLP GEMM) kernel names of their own, so that a profile lists them apart.
+template <class T, int EPI, int OUT, bool GATHER, bool FAST, int TAG>
 __global__ __launch_bounds__(T::NT, T::MINBLK) void gemm_bf16_kernel(GemmArgs g) {
   // + room for a wider rotary table (QKV epilogue) + per-row scales of the epilogue
   __shared__ __attribute__((aligned(1024))) char lds[T::LDS_BYTES + lds_extra<T, EPI>() + T::BM * 4];
@@ -790,11 +767,14 @@ static void launch_cfg(const GemmArgs& g, hipStream_t s) {
   a.group_m = std::min(a.group_m, tiles_m);
   if constexpr (!GATHER) {
     if (g.overread_ok && g.K % T::BK == 0) {
-      hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, false, true>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
+      if (EPI == EPI_RESIDUAL && g.name_tag == 1)
+        hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, false, true, (EPI == EPI_RESIDUAL ? 1 : 0)>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
+      else
+        hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, false, true, 0>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
       return;
     }
   }
-  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, GATHER, false>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
+  hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, GATHER, false, 0>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
 }
 
 //            BM   BN  BK  WM WN MINBLK
@@ -802,13 +782,6 @@ using T0 = Tile<256, 256, 64, 2, 4, 1>;   // 8 waves, 128x64 wave tiles, 128 KB 
 using T2 = Tile<256, 128, 64, 2, 2, 1>;   // 4 waves, 128x64 wave tiles, 96 KB LDS
 using T4 = Tile<128, 128, 64, 2, 2, 2>;   // 4 waves, 64x64 wave tiles, 64 KB LDS, two blocks per CU
 using T5 = Tile<320, 256, 64, 2, 4, 1>;   // 8 waves, 160x64 wave tiles, 144 KB LDS
-
-// Tuning and test knob: EPD_GEMM_TILE = 0, 2, 4 or 5 forces that tile variant for every bf16
-// GEMM launched afterwards (read at every launch, so one process can try several).
-static int forced_tile() {
-  const char* e = getenv("EPD_GEMM_TILE");
-  return e ? atoi(e) : -1;
-}
 
 // Tile choice.  The 256 x 256 tile halves the operand traffic per flop and is the fastest
 // main loop, but runs one block per compute unit; the 128 x 128 tile runs two, which hides
@@ -820,7 +793,7 @@ static int forced_tile() {
 // tile is kept unless another is clearly (5 %) cheaper.
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
-  int t = (g.tile_cfg & 255) > 0 ? (g.tile_cfg & 255) - 1 : forced_tile();
+  int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1;   // tile_cfg: set by the tuning hook of the C ABI
   if (t != 0 && t != 2 && t != 4 && t != 5) {
     const long cus = num_cus();
     auto cost = [&](int bm, int bn, int blocks, double rate) {

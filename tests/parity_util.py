@@ -41,13 +41,17 @@ def check(cfg, got, ref, what=""):
     return mabs, cos, rel
 
 
-def run_gpu(cfg, gw, layers, patches, cu, grid, want_hidden=False, max_tokens=None, segments=None, items=None):
-    """One epd_encode call through the C ABI; returns float64 arrays."""
+def run_gpu(cfg, gw, layers, patches, cu, grid, want_hidden=False, max_tokens=None, segments=None, items=None,
+            gemm_tile=-1, attn_groups=0):
+    """One epd_encode call through the C ABI; returns float64 arrays.  gemm_tile / attn_groups
+    force a kernel variant through the library's tuning hook (-1 / 0 = its own choice)."""
     import torch
     from paper_2601_11590_amd import binding as B
     enc = B.EpdEncoder(cfg, gw, layers, max_tokens=max_tokens or int(patches.shape[0]),
                        max_segments=segments or max(1, len(cu) - 1), max_items=items or max(1, len(grid)))
     try:
+        if gemm_tile != -1 or attn_groups != 0:
+            enc.set_tuning(gemm_tile, attn_groups)
         p = B.to_device_patches(patches, cfg.dtype)
         y = enc.encode(p, cu, grid)
         torch.cuda.synchronize()

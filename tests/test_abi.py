@@ -120,6 +120,29 @@ def test_create_rejects_token_counts_beyond_the_32_bit_k_offsets_of_bf16_attenti
     assert B.epd_encode_workspace_bytes(B.make_cfg(TINY, (1 << 30) // 64 - 1, 4, 4)) > 0
 
 
+def test_create_rejects_segment_counts_beyond_the_32_bit_offsets_of_the_transposed_v_rows():
+    # a head's V^T rows are head_dim rows of (max_tokens + 128 * max_segments) bf16 columns,
+    # addressed with 32-bit byte offsets: many segments alone can push that past 2^32
+    wide = TINY.replace(hidden=128, num_heads=1, head_dim=128, rope_pairs=(0, 32, 32))
+    c = B.make_cfg(wide, 1 << 16, 140000, 4)
+    assert B.epd_encode_workspace_bytes(c) == 0
+    c = B.make_cfg(wide, 1 << 16, 100000, 4)
+    assert B.epd_encode_workspace_bytes(c) > 0
+    h = C.c_void_p()
+    c = B.make_cfg(wide, 1 << 16, 140000, 4)
+    assert B.lib.epd_encode_create(C.byref(c), C.byref(h)) == B.EPD_ERR_UNSUPPORTED
+    assert "max_segments" in B.epd_encode_last_error(None)
+
+
+def test_built_library_carries_the_hash_of_its_sources():
+    """The binary the tests load is the one built from the sources as they stand: build() stores a
+    hash of csrc/, the public header and the flags next to the library, and library_path() builds
+    again when that stamp differs from the tree."""
+    from paper_2601_11590_amd import build as bld
+    assert os.path.exists(bld.LIB) and bld.built_hash() == bld.source_hash()
+    assert bld.source_hash(("-DX",)) != bld.source_hash()
+
+
 def test_create_rejects_bad_pointers_enums_and_workspace():
     st, msg = _create_error(TINY, lambda c: setattr(c, "struct_size", 12))
     assert st == B.EPD_ERR_INVALID_ARG and "struct_size" in msg
@@ -140,6 +163,7 @@ def test_create_rejects_bad_pointers_enums_and_workspace():
     assert B.lib.epd_encode(None, None, None, 0, None, 0, None, None) == B.EPD_ERR_INVALID_ARG
     assert B.lib.epd_encode_destroy(None) == B.EPD_ERR_INVALID_ARG
     assert B.lib.epd_encode_set_timing(None, 0) == B.EPD_ERR_INVALID_ARG
+    assert B.lib.epd_encode_set_tuning(None, -1, 0) == B.EPD_ERR_INVALID_ARG
     assert B.epd_encode_workspace_bytes(B.make_cfg(TINY.replace(head_dim=60), 64, 1, 1)) == 0
 
 

@@ -1,0 +1,216 @@
+"""GPU parity of every compiled variant of the bf16 flash-attention kernel (csrc/attn_bf16.hip)
+on inputs that drive its online softmax through the branches ordinary N(0, 0.02) weights never
+reach: the running reference moves after the first key tile, the output accumulators (and, where
+the kernel keeps them, the accumulator preset and the ones-row denominator) are rescaled, and
+probabilities over- or underflow unless the reference is subtracted.
+
+Two kinds of input, both compared element by element with the fp64 oracle at the stated bf16
+tolerances (per-token cosine >= 0.999, max-norm relative error <= 2e-2):
+
+  sharp    weights of std 0.05 and the Q rows scaled by the gain that brings the logits to a
+           standard deviation of 8 log2 units (they are linear in that gain), so the maximum of a
+           row keeps rising by more than the kernel's slack (8 log2 units) in later key tiles.
+           (Sharper is not a fair test of a kernel: with logits of std 12 the bf16 rounding of Q,
+           K and V alone -- the fp64 oracle fed with rounded operands -- already misses the 2e-2
+           bound, 2.7e-2 at head dim 72; at std 8 that floor is 0.7-1.2e-2.)
+           Each case counts, from the oracle's own scores, the (row, head) pairs whose reference
+           moves after the first tile and requires that there are many.
+  outlier  one designated key per segment whose logit stands ~ +140 above all others for EVERY
+           query row of the segment (exp(140) overflows fp32 if the maximum is not subtracted;
+           everything else underflows to 0): early in the segment (first key tile: all later
+           tiles underflow) or late (last key tile: the reference jumps by ~ 200 log2 units and
+           everything accumulated before is scaled to 0).
+
+Variants (template arguments <head dim, 32-row groups per wave, blocks per CU, ones row>):
+  <32,1,4,0> <64,1,4,0>   d <= 64, segments <= 1024: reference subtracted per score, VALU sum
+  <32,2,2,0> <64,2,2,0>   d <= 64, a segment > 1024: two groups per wave, per-group alpha
+  <72,1,2,1> <80,1,2,1>   accumulator-preset reference (CREF) + ones-row denominator (SUMROW)
+  <96,1,2,0> <128,1,2,0>  accumulator-preset reference, VALU sum
+"""
+
+import numpy as np
+import pytest
+
+from oracle import vit_encode as O
+from paper_2601_11590_amd import workloads as W
+from parity_util import check, log, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+K_LAG = 8.0            # slack of the kernel's running reference, log2 units
+KEY_TILE = 64
+
+# segments of 13.8, 9 and 1.2 key tiles (none a multiple of 64 except 576), all <= 1024
+SHORT = [(1, 26, 34), (1, 16, 36), (1, 2, 38)]          # 884 + 576 + 76 tokens
+# a segment > 1024 tokens switches d <= 64 to two query groups per wave: 17.8, 10 and 0.9 tiles
+LONG = [(1, 30, 38), (1, 20, 32), (1, 6, 10)]           # 1140 + 640 + 60 tokens
+# per-frame segments: 2 x 576 and 3 x 132 tokens
+FRAMES = [(2, 24, 24), (3, 6, 22)]
+
+
+def cfg_for(d, **kw):
+    base = dict(name="attn-d%d" % d, dtype="bf16", num_layers=2, hidden=2 * d, num_heads=2, head_dim=d,
+                mlp_dim=4 * d, patch=4, temporal_patch=1, norm="rmsnorm", rope="2d",
+                rope_pairs=(0, d // 4, d // 2 - d // 4), out_dim=96, seed=40 + d)
+    base.update(kw)
+    return W.EncoderConfig(**base)
+
+
+def first_layer_scores(cfg, gw, lw, patches, cu, grid):
+    """log2-unit scores of layer 0 per (segment, head), from the oracle's own functions."""
+    x = O.linear(patches, gw["patch_w"], gw.get("patch_b"))
+    a = O.norm(cfg, x, lw["norm1_g"], lw.get("norm1_b"))
+    qkv = O.linear(a, lw["qkv_w"], lw.get("qkv_b"))
+    T, H, d = x.shape[0], cfg.num_heads, cfg.head_dim
+    q, k = qkv[:, :H * d].reshape(T, H, d), qkv[:, H * d:2 * H * d].reshape(T, H, d)
+    if cfg.rope != "none":
+        th = O.rotary_angles(O.token_coords(grid), cfg.rope_pairs, cfg.rope_base)
+        q, k = O.apply_rotary(q, th), O.apply_rotary(k, th)
+    out = []
+    for s in range(len(cu) - 1):
+        a0, b0 = int(cu[s]), int(cu[s + 1])
+        for h in range(H):
+            out.append((q[a0:b0, h] @ k[a0:b0, h].T) * (np.log2(np.e) / np.sqrt(d)))
+    return out
+
+
+def rows_whose_reference_moves(scores):
+    """(rows whose lagging reference moves after the first key tile, rows) under the kernel's
+    rule: the reference follows the running maximum only when it trails it by more than K_LAG."""
+    moved = total = 0
+    for s in scores:
+        n = s.shape[1]
+        if n <= KEY_TILE:
+            continue
+        ref = s[:, :KEY_TILE].max(axis=1)
+        hit = np.zeros(s.shape[0], bool)
+        for t0 in range(KEY_TILE, n, KEY_TILE):
+            mx = s[:, t0:t0 + KEY_TILE].max(axis=1)
+            lag = mx > ref + K_LAG
+            hit |= lag
+            ref = np.where(lag, mx, ref)
+        moved += int(hit.sum())
+        total += s.shape[0]
+    return moved, total
+
+
+def sharp_case(d, grids, segments="item", attn_groups=0, **kw):
+    cfg = cfg_for(d, **kw)
+    gw = W.global_weights(cfg, 0.05)
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids, segments)
+    plain = np.concatenate([s.ravel() for s in first_layer_scores(cfg, gw, W.layer_weights(cfg, 0, 0.05), patches, cu, grid)])
+    q_gain = float(8.0 / plain.std())
+    layers = [W.layer_weights(cfg, l, 0.05, q_gain) for l in range(cfg.num_layers)]
+    moved, total = rows_whose_reference_moves(first_layer_scores(cfg, gw, layers[0], patches, cu, grid))
+    log("case %s sharp grids=%s segments=%s groups=%d q_gain=%g: reference moves after the first key tile in %d of %d (row, head) pairs"
+        % (cfg.name, grids, segments, attn_groups, q_gain, moved, total))
+    assert moved >= total // 8, "the input does not exercise the rescale path"
+    ref, ref_h = O.encode(cfg, gw, layers, patches, cu, grid, return_hidden=True)
+    got, got_h = run_gpu(cfg, gw, layers, patches, cu, grid, want_hidden=True, attn_groups=attn_groups)
+    check(cfg, got_h, ref_h, "hidden")
+    check(cfg, got, ref, "output")
+
+
+# ---- sharp softmax: every variant, >= 8 key tiles per segment, ragged last tiles
+
+@pytest.mark.parametrize("d", [32, 64])
+def test_sharp_softmax_one_group_per_wave_small_head_dims(d):
+    # attn_bf16_kernel<d,1,4,false>: the !CREF branch of `compute` (alpha = exp2(mrun - mnew),
+    # delta subtracted per score, o *= alpha and lrun = lrun * alpha + psum when a row moved)
+    sharp_case(d, SHORT)
+
+
+@pytest.mark.parametrize("d", [32, 64])
+def test_sharp_softmax_two_groups_per_wave_long_segments(d):
+    # a 1140-token segment selects attn_bf16_kernel<d,2,2,false>: both 32-row groups of a wave
+    # carry their own mrun / lrun / alpha, and `any_moved` is the wave-wide vote over both
+    sharp_case(d, LONG)
+
+
+@pytest.mark.parametrize("d", [32, 64])
+def test_sharp_softmax_two_groups_forced_on_short_segments(d):
+    # the same kernel on segments whose last query tile is mostly empty (76 of 256 rows): waves
+    # without any query row only load and synchronise
+    sharp_case(d, SHORT, attn_groups=2)
+
+
+@pytest.mark.parametrize("d", [72, 80])
+def test_sharp_softmax_preset_reference_and_ones_row(d):
+    # attn_bf16_kernel<d,1,2,true>: CREF (scores accumulate onto the preset -reference; when a
+    # row moves, delta = mx is subtracted, o *= alpha and the preset is renewed from mrun) and
+    # SUMROW (row d of O^T accumulates the denominator and is rescaled with the outputs)
+    sharp_case(d, LONG, norm="layernorm")
+
+
+@pytest.mark.parametrize("d", [96, 128])
+def test_sharp_softmax_preset_reference_vector_sum(d):
+    # attn_bf16_kernel<d,1,2,false>: CREF with the denominator kept per lane
+    # (lrun = lrun * alpha + psum) and merged across the wave halves at the end
+    sharp_case(d, LONG, rope="3d", rope_pairs=(d // 8, d // 4 - d // 8, d // 4))
+
+
+@pytest.mark.parametrize("d", [64, 72, 128])
+def test_sharp_softmax_per_frame_segments(d):
+    # one segment per frame (2 x 576 and 3 x 132 tokens): query tiles end inside a 128-row tile
+    # at every frame boundary and every segment starts at a padded column of the V^T buffer
+    sharp_case(d, FRAMES, segments="frame")
+
+
+# ---- one dominant logit per row
+
+def outlier_case(d, grids, where):
+    """One layer without rotary.  Patch element 0 is zero everywhere except at the designated
+    token of each segment, column 0 of the patch embedding is a +-1 pattern s, and the first
+    key channel of every head also reads a * <s, xn> / sqrt(D): after the norm the designated
+    token has <s, xn> ~ sqrt(D) where every other token has ~ N(0, 1).  The first query channel of
+    every head gets a constant bias c, so every query scores the designated key c * a * sqrt(D) /
+    sqrt(d) ~ 140 (natural units) above the rest."""
+    cfg = cfg_for(d, num_layers=1, rope="none", rope_pairs=(0, 0, 0))
+    D, H = cfg.hidden, cfg.num_heads
+    gw = W.global_weights(cfg)
+    lw = W.layer_weights(cfg, 0)
+    patches = W.packed_patches(cfg, grids).copy()
+    cu, grid = W.metadata(grids)
+    rng = np.random.default_rng(7)
+    s = rng.choice([-1.0, 1.0], size=D).astype(np.float32)
+    gw["patch_w"][:, 0] = s
+    patches[:, 0] = 0.0
+    marked = []
+    for i in range(len(cu) - 1):
+        n = int(cu[i + 1] - cu[i])
+        j = int(cu[i]) + (min(5, n - 1) if where == "early" else n - 1 - min(5, n - 1))
+        patches[j, 0] = 64.0
+        marked.append(j)
+    a = 4.0
+    c = W.round_to_dtype(np.float32([140.0 * np.sqrt(d) / (a * np.sqrt(D))]), cfg.dtype)[0]
+    for h in range(H):
+        lw["qkv_w"][D + h * d, :] += np.float32(a / np.sqrt(D)) * s           # first K channel of head h
+        lw["qkv_b"][h * d] += c                                               # first Q channel of head h
+    lw["qkv_w"] = W.round_to_dtype(lw["qkv_w"], cfg.dtype)
+    lw["qkv_b"] = W.round_to_dtype(lw["qkv_b"], cfg.dtype)
+    scores = first_layer_scores(cfg, gw, lw, patches, cu, grid)
+    gaps = []
+    for idx, sc in enumerate(scores):
+        seg = idx // H
+        col = marked[seg] - int(cu[seg])
+        if sc.shape[1] > 1:
+            gaps.append((sc[:, col] - np.delete(sc, col, axis=1).max(axis=1)).min())
+    gap_nat = min(gaps) * np.log(2.0)
+    log("case %s outlier %s grids=%s: the designated key leads every row by >= %.1f (natural units)" % (cfg.name, where, grids, gap_nat))
+    assert gap_nat >= 60.0, "the designated logit does not stand out"
+    ref, ref_h = O.encode(cfg, gw, [lw], patches, cu, grid, return_hidden=True)
+    got, got_h = run_gpu(cfg, gw, [lw], patches, cu, grid, want_hidden=True)
+    check(cfg, got_h, ref_h, "hidden")
+    check(cfg, got, ref, "output")
+
+
+@pytest.mark.parametrize("where", ["early", "late"])
+@pytest.mark.parametrize("d,grids", [(32, SHORT), (64, SHORT), (64, LONG), (72, LONG), (80, SHORT), (96, SHORT), (128, LONG)],
+                         ids=["d32", "d64", "d64-two-groups", "d72", "d80", "d96", "d128"])
+def test_one_dominant_logit_per_row(d, grids, where):
+    # "late": the reference jumps by ~ 200 log2 units in the last key tile, alpha underflows to 0
+    # and everything accumulated so far (outputs, denominator, ones row) must vanish without a
+    # NaN; "early": all later tiles contribute exp2(-200) = 0 and must leave the result alone.
+    # Reaches the rescale branch of every variant (`if (any_moved)` in `compute`).
+    outlier_case(d, grids, where)

@@ -218,6 +218,31 @@ def test_empty_or_zero_sized_calls_are_rejected():
         enc.close()
 
 
+def test_tuning_hook_rejects_what_has_no_kernel_and_keeps_the_result_within_tolerance():
+    from paper_2601_11590_amd import binding as B
+    cfg = small("bf16", num_heads=2, head_dim=128, rope="3d", rope_pairs=(16, 24, 24))
+    enc, gw, layers = make_encoder(cfg, 512)
+    try:
+        for tile, groups, status in ((3, 0, B.EPD_ERR_INVALID_ARG), (-2, 0, B.EPD_ERR_INVALID_ARG), (0, 3, B.EPD_ERR_INVALID_ARG),
+                                     (-1, 2, B.EPD_ERR_UNSUPPORTED)):      # two query groups exist for head_dim <= 64 only
+            with pytest.raises(B.EpdError) as ei:
+                enc.set_tuning(tile, groups)
+            assert ei.value.status == status, str(ei.value)
+        patches = W.packed_patches(cfg, GRIDS)
+        cu, grid = W.metadata(GRIDS)
+        ref = O.encode(cfg, gw, layers, patches, cu, grid)
+        auto = run(enc, cfg, patches, cu, grid)
+        enc.set_tuning(2, 1)
+        forced = run(enc, cfg, patches, cu, grid)
+        enc.set_tuning(-1, 0)
+        again = run(enc, cfg, patches, cu, grid)
+        check(cfg, auto, ref, "automatic")
+        check(cfg, forced, ref, "tile 256x128 forced")
+        assert np.array_equal(auto, again), "switching the hook off must restore the first result bit for bit"
+    finally:
+        enc.close()
+
+
 def test_c3_full_varlen_batch_one_layer():
     # all 32 images, 73 896 tokens (the maximum batch of the benchmark configurations), one layer
     shaped_case(W.C3.replace(num_layers=1), W.grids_for(W.C3), "32 varlen images, 73896 tokens, L=1")

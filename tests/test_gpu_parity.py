@@ -21,12 +21,12 @@ def case(cfg, grids, segments="item", q_gain=1.0, std=0.02):
     return gw, layers, patches, cu, grid
 
 
-def parity(cfg, grids, **kw):
-    log("case %s dtype=%s L=%d D=%d d=%d F=%d grids=%s %s" % (cfg.name, cfg.dtype, cfg.num_layers, cfg.hidden,
-                                                              cfg.head_dim, cfg.mlp_dim, grids[:6], kw))
+def parity(cfg, grids, gemm_tile=-1, attn_groups=0, **kw):
+    log("case %s dtype=%s L=%d D=%d d=%d F=%d grids=%s %s tile=%d groups=%d"
+        % (cfg.name, cfg.dtype, cfg.num_layers, cfg.hidden, cfg.head_dim, cfg.mlp_dim, grids[:6], kw, gemm_tile, attn_groups))
     gw, layers, patches, cu, grid = case(cfg, grids, **kw)
     ref, ref_h = O.encode(cfg, gw, layers, patches, cu, grid, return_hidden=True)
-    got, got_h = run_gpu(cfg, gw, layers, patches, cu, grid, want_hidden=True)
+    got, got_h = run_gpu(cfg, gw, layers, patches, cu, grid, want_hidden=True, gemm_tile=gemm_tile, attn_groups=attn_groups)
     assert got.shape == ref.shape
     check(cfg, got_h, ref_h, "hidden")
     return check(cfg, got, ref, "output")
@@ -139,13 +139,12 @@ def test_bf16_many_tiles():
 
 
 @pytest.mark.parametrize("tile", [0, 2, 4, 5])
-def test_bf16_every_gemm_tile_variant(tile, monkeypatch):
-    # each tile shape of the bf16 GEMM forced in turn (the library reads EPD_GEMM_TILE at every
-    # launch): 1304 tokens = several row tiles of each with a ragged last one; hidden 512 so
-    # that the 256-wide tiles keep whole Q|K column tiles
-    monkeypatch.setenv("EPD_GEMM_TILE", str(tile))
+def test_bf16_every_gemm_tile_variant(tile):
+    # each tile shape of the bf16 GEMM forced in turn through the tuning hook: 1304 tokens =
+    # several row tiles of each with a ragged last one; hidden 512 so that the 256-wide tiles
+    # keep whole Q|K column tiles
     cfg = small("bf16", hidden=512, num_heads=8, mlp_dim=1088, out_dim=328)
-    parity(cfg, [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8), (1, 4, 16)])
+    parity(cfg, [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8), (1, 4, 16)], gemm_tile=tile)
 
 
 def test_c2_width_two_layers_full_batch():
