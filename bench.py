@@ -1,17 +1,22 @@
 #!/usr/bin/env python3
 """Throughput of the Encode stage (ViT forward, V_m = E(I_m); paper section 3.1, Eq. 1) on one
-MI355X: visual tokens per second on the 24-layer bf16 encoder with a batch of 8 images of
-448 x 448 (6272 packed patch tokens -> 1568 visual tokens), synthetic seeded inputs.
+MI355X: visual tokens per second, synthetic seeded inputs.
 
-One "step" is one epd_encode call: plan, patch embedding, 24 transformer blocks, final norm,
-2x2 merge and projection, with the packed patches and weights already resident in HBM.
+The headline workload is the largest single-GPU benchmark configuration, C5: the 45-layer
+video encoder (hidden 3200, 25 heads x 128, MLP 12800, patch 14 x temporal 2, 3-D rotary) on
+four clips of 16 frames at 448 x 448 -- 32 768 packed patch tokens -> 8192 visual tokens.  One
+"step" is one epd_encode call: plan, patch embedding, all transformer blocks, final norm, 2x2
+merge and projection, with the packed patches and weights already resident in HBM.  The other
+bf16 configurations (C2, C3, C4) are timed in the same run, briefly, and reported in the
+"others" block of the line.
 
-Prints ONE JSON line on stdout; progress and the per-step table go to stderr.
+Prints ONE JSON line on stdout; progress and the per-step tables go to stderr.
 """
 
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -21,28 +26,14 @@ import numpy as np
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+ROOT = os.path.dirname(os.path.abspath(__file__))
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(cfg, gw, layers, patches, cu, grid, gpu_out, n_items):
-    """Time the CPU oracle, as it stands, on the first n_items images of the same batch."""
-    from oracle import vit_encode as O
-    from paper_2601_11590_amd import workloads as W
-    grids = [tuple(int(v) for v in g) for g in grid[:n_items]]
-    T = W.num_tokens(grids)
-    Tm = W.num_merged_tokens(grids, cfg.merge)
-    cu1, g1 = W.metadata(grids)
-    t0 = time.perf_counter()
-    ref = O.encode(cfg, gw, layers, patches[:T], cu1, g1)
-    dt = time.perf_counter() - t0
-    got = gpu_out[:Tm].astype(np.float64)
-    cos = (got * ref).sum(-1) / (np.linalg.norm(got, axis=-1) * np.linalg.norm(ref, axis=-1))
-    rel = np.abs(got - ref).max(-1) / np.abs(ref).max(-1)
-    log("[bench] oracle on %d image(s): %.2f s; GPU rows vs oracle: min cos %.6f, max rel %.3e"
-        % (n_items, dt, cos.min(), rel.max()))
+def host_cores():
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
@@ -50,139 +41,131 @@ def cpu_baseline(cfg, gw, layers, patches, cu, grid, gpu_out, n_items):
     env = os.environ.get("OMP_NUM_THREADS")
     if env and env.isdigit():
         cores = min(cores, int(env))
-    return {"value": Tm / dt, "unit": "visual tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "first %d of the 8 images (%d patch tokens -> %d visual tokens), all %d layers, "
-                      "fp64 NumPy, one run" % (n_items, T, Tm, cfg.num_layers),
-            "seconds": dt, "parity_min_cos": float(cos.min()), "parity_max_rel": float(rel.max())}
+    return cores
 
 
-def colocation():
-    """Operator-level co-location (paper section 3.5, "Physical Co-Location and Spatial Multiplexing"):
-    how much one kind of work slows down when another kind runs beside it on the same GPU, for work
-    bound by different units.  Rows = the measured operator, columns = the neighbour; entries =
-    time beside the neighbour / time alone.  Prints one JSON line."""
+def parity_numbers(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    cos = (got * ref).sum(-1) / (np.linalg.norm(got, axis=-1) * np.linalg.norm(ref, axis=-1))
+    rel = np.abs(got - ref).max(-1) / np.abs(ref).max(-1)
+    return float(cos.min()), float(rel.max())
+
+
+def cpu_baseline_full(cfg, gw, layers, patches, grid, gpu_out, n_items):
+    """The CPU oracle, as it stands, on the first n_items items of the batch at full depth
+    (configurations the oracle finishes in seconds)."""
+    from oracle import vit_encode as O
+    from paper_2601_11590_amd import workloads as W
+    grids = [tuple(int(v) for v in g) for g in grid[:n_items]]
+    T, Tm = W.num_tokens(grids), W.num_merged_tokens(grids, cfg.merge)
+    cu1, g1 = W.metadata(grids)
+    t0 = time.perf_counter()
+    ref = O.encode(cfg, gw, layers, patches[:T], cu1, g1)
+    dt = time.perf_counter() - t0
+    cos, rel = parity_numbers(gpu_out[:Tm], ref)
+    log("[bench] oracle on %d item(s), %d layers: %.2f s; GPU rows vs oracle: min cos %.6f, max rel %.3e" % (n_items, cfg.num_layers, dt, cos, rel))
+    return {"value": Tm / dt, "unit": "visual tokens/s", "cores": host_cores(), "kind": "oracle",
+            "sample": "first %d of the %d items (%d patch tokens -> %d visual tokens), all %d layers, fp64 NumPy, one run"
+                      % (n_items, len(grid), T, Tm, cfg.num_layers),
+            "seconds": dt, "parity_min_cos": cos, "parity_max_rel": rel}
+
+
+def cpu_baseline_depth_sample(cfg, gw, layer0, patches, grid):
+    """The CPU oracle, as it stands, on the first item of the batch with 0 and with 1 of the
+    configuration's layers (a full-depth run takes the oracle tens of minutes); the rate at
+    full depth is the linear extrapolation in depth, every layer having the same shape."""
+    from oracle import vit_encode as O
+    from paper_2601_11590_amd import workloads as W
+    g0 = [tuple(int(v) for v in grid[0])]
+    T, Tm = W.num_tokens(g0), W.num_merged_tokens(g0, cfg.merge)
+    cu1, g1 = W.metadata(g0)
+    t = time.perf_counter()
+    O.encode(cfg.replace(num_layers=0), gw, [], patches[:T], cu1, g1)
+    t_l0 = time.perf_counter() - t
+    t = time.perf_counter()
+    O.encode(cfg.replace(num_layers=1), gw, [layer0], patches[:T], cu1, g1)
+    t_l1 = time.perf_counter() - t
+    per_layer = max(t_l1 - t_l0, 1e-9)
+    full = t_l0 + cfg.num_layers * per_layer
+    log("[bench] oracle on item 0 (%d tokens): %.2f s with 0 layers, %.2f s with 1 layer -> %.0f s extrapolated to %d layers"
+        % (T, t_l0, t_l1, full, cfg.num_layers))
+    return {"value": Tm / full, "unit": "visual tokens/s", "cores": host_cores(), "kind": "oracle",
+            "sample": "item 0 of %d (%d patch tokens -> %d visual tokens): the oracle timed once with 0 layers (%.2f s) and once "
+                      "with 1 layer (%.2f s) of the %d; value = %d / (t0 + %d (t1 - t0)), a linear extrapolation in depth "
+                      "(all layers have one shape), fp64 NumPy" % (len(grid), T, Tm, t_l0, t_l1, cfg.num_layers, Tm, cfg.num_layers),
+            "seconds": t_l0 + t_l1, "extrapolated_full_depth_seconds": full}
+
+
+def stored_rows_parity(name, gpu_out):
+    """Full-depth parity against the oracle rows stored under tests/golden/ (C4, C5)."""
+    path = os.path.join(ROOT, "tests", "golden", "%s_full_depth_rows.npz" % name.lower())
+    if not os.path.exists(path):
+        return None
+    z = np.load(path, allow_pickle=False)
+    rows, first = z["rows"], int(z["first_row_in_batch"])
+    cos, rel = parity_numbers(gpu_out[first + rows], z["values"])
+    log("[bench] %s full depth vs %d stored oracle rows: min cos %.6f, max rel %.3e" % (name, len(rows), cos, rel))
+    return {"rows": int(len(rows)), "min_cos": cos, "max_rel": rel, "source": "tests/golden/%s" % os.path.basename(path)}
+
+
+def flops_per_call(cfg, T, Tm, cu):
+    D, F, L = cfg.hidden, cfg.mlp_dim, cfg.num_layers
+    attn = L * sum(4.0 * float(cu[i + 1] - cu[i]) ** 2 * D for i in range(len(cu) - 1))
+    return (2.0 * T * cfg.patch_dim * D + L * (8.0 * T * D * D + 4.0 * T * D * F) + attn
+            + 2.0 * Tm * (cfg.merge ** 2 * D) * cfg.out_dim), attn
+
+
+def stored_traffic(name, step):
+    """HBM-side bytes per launch of `step` from the rocprofv3 --pmc summary under profiles/ (they
+    cannot be collected in-process).  The summary carries the hash of the kernel sources it was
+    measured on; a summary of other sources is not used."""
+    from paper_2601_11590_amd import build as bld
+    path = os.path.join(ROOT, "profiles", "%s_bench_hbm_traffic.txt" % name.lower())
+    if not os.path.exists(path):
+        return None, "no counter summary for %s under profiles/" % name
+    val, stamp = None, None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == "SOURCE_HASH":
+            stamp = parts[1]
+        if len(parts) >= 3 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == step:
+            val = float(parts[2])
+    if stamp != bld.source_hash():
+        return None, "profiles/%s was measured on other kernel sources (hash differs): dropped" % os.path.basename(path)
+    return val, "profiles/%s" % os.path.basename(path)
+
+
+def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="item", keep_inputs=False):
+    """Times `steps` epd_encode calls of configuration `name`.  Returns a dict of results."""
     import torch
     from paper_2601_11590_amd import binding as B, workloads as W
-    cfg = W.C2
+    cfg = W.CONFIGS[name]
     grids = W.grids_for(cfg)
+    if layers_override is not None:
+        cfg = cfg.replace(num_layers=layers_override)
     T, Tm = W.num_tokens(grids), W.num_merged_tokens(grids, cfg.merge)
-    gw = W.global_weights(cfg)
-    layers = [W.layer_weights(cfg, l) for l in range(cfg.num_layers)]
-    patches = B.to_device_patches(W.packed_patches(cfg, grids), cfg.dtype)
-    cu, grid = W.metadata(grids)
-    encs = [B.EpdEncoder(cfg, gw, layers, max_tokens=T, max_segments=len(grids), max_items=len(grids)) for _ in range(2)]
-    outs = [torch.empty((Tm, cfg.out_dim), dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]
-    src = [torch.ones(1 << 27, dtype=torch.float32, device="cuda:0") for _ in range(2)]     # 512 MiB each
-    dst = [torch.empty_like(x) for x in src]
-    stores = [B.MMStore(2 << 20) for _ in range(2)]
-    blob = [torch.randint(0, 256, (64 << 20,), dtype=torch.uint8, device="cuda:0") for _ in range(2)]
-    nrm = [torch.randn((1 << 16, 1024), dtype=torch.float32, device="cuda:0") for _ in range(2)]
-
-    # one unit of each kind of work, on the current stream; slot 0 = measured, 1 = neighbour
-    ops = {
-        "encode (matrix cores + exp)": lambda i: encs[i].encode(patches, cu, grid, outs[i]),
-        "copy 512 MiB (HBM)": lambda i: dst[i].copy_(src[i]),
-        "hash 64 MiB (integer ALU)": lambda i: stores[i].hash(blob[i], [0, blob[i].numel()], [1]),
-        "softmax 64k x 1024 fp32 (HBM + exp)": lambda i: torch.softmax(nrm[i], dim=-1),
-    }
-    # the hash call waits for its keys (it is synchronous by contract), so it cannot sit in a queue
-    # beside something else: it is measured, never a neighbour
-    names = list(ops)
-    neighbours = [n for n in names if not n.startswith("hash")]
-    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
-    reps = {"encode (matrix cores + exp)": 6, "copy 512 MiB (HBM)": 60, "hash 64 MiB (integer ALU)": 20,
-            "softmax 64k x 1024 fp32 (HBM + exp)": 60}
-
-    def timed(a, b):
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        if b is not None:
-            with torch.cuda.stream(s2):
-                for _ in range(reps[b] * 6):          # a queue several times longer than the measured run
-                    ops[b](1)
-        with torch.cuda.stream(s1):
-            ops[a](0)
-            e0.record()
-            for _ in range(reps[a]):
-                ops[a](0)
-            e1.record()
-        e1.synchronize()
-        ms = e0.elapsed_time(e1) / reps[a]
-        torch.cuda.synchronize()
-        return ms
-
-    alone = {a: min(timed(a, None) for _ in range(2)) for a in names}
-    table = {a: {b: timed(a, b) / alone[a] for b in neighbours} for a in names}
-    for a in names:
-        log("[colocation] %-38s alone %8.3f ms | " % (a, alone[a]) + "  ".join("beside %s: x%.2f" % (b.split(" (")[0], table[a][b]) for b in neighbours))
-    print(json.dumps({"experiment": "operator co-location slowdown (time beside neighbour / time alone), one MI355X, two streams of default priority",
-                      "alone_ms": alone, "slowdown": table}), flush=True)
-    for e in encs:
-        e.close()
-    for st in stores:
-        st.close()
-
-
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C2", help="C2 (headline) | C3 | C4 | C5 (other single-GPU shapes)")
-    ap.add_argument("--layers", type=int, default=None, help="override depth (non-headline experiments only)")
-    ap.add_argument("--cpu-items", type=int, default=8, help="images of the batch the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="only run a plain 1 GiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--in-flight", type=int, default=1,
-                    help="batches in flight on separate streams (serving mode; default 1 = one stream)")
-    ap.add_argument("--colocation", action="store_true",
-                    help="only run the operator co-location experiment (section 3.5) and print its table")
-    args = ap.parse_args()
-    if args.colocation:
-        if args.gpus != 1:
-            log("bench.py: one GPU only"); sys.exit(2)
-        colocation()
-        return
-    if args.copy_calibration:
-        import torch
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        log("[bench] copied 5 x 1 GiB (reads 1 GiB and writes 1 GiB per launch)")
-        return
-    if args.gpus != 1:
-        log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
-            "--gpus %d is not supported. Items would shard across GPUs by image with replicated "
-            "weights; nothing here launches more than one rank." % args.gpus)
-        sys.exit(2)
-
-    import torch
-    from paper_2601_11590_amd import binding as B, workloads as W
-
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    cfg = W.CONFIGS[args.config]
-    grids = W.grids_for(cfg)
-    if args.layers is not None:
-        cfg = cfg.replace(num_layers=args.layers)
-    T, Tm = W.num_tokens(grids), W.num_merged_tokens(grids, cfg.merge)
-    log("[bench] %s: %d items, T=%d patch tokens -> %d visual tokens, L=%d" % (cfg.name, len(grids), T, Tm, cfg.num_layers))
-
+    cu, grid = W.metadata(grids, segments)
+    log("[bench] %s: %d items, %d segments, T=%d patch tokens -> %d visual tokens, L=%d" % (cfg.name, len(grids), len(cu) - 1, T, Tm, cfg.num_layers))
     t0 = time.perf_counter()
     gw = W.global_weights(cfg)
-    layers = [W.layer_weights(cfg, l) for l in range(cfg.num_layers)]
     patches = W.packed_patches(cfg, grids)
-    cu, grid = W.metadata(grids)
-    log("[bench] inputs generated in %.1f s" % (time.perf_counter() - t0))
+    layer0 = W.layer_weights(cfg, 0) if cfg.num_layers > 0 else None
+    kept_layers = []
 
-    enc = B.EpdEncoder(cfg, gw, layers, max_tokens=T, max_segments=len(cu) - 1, max_items=len(grids))
+    def layer_stream():     # one layer at a time: 45 layers of C5 would be 22 GB of float32 on the host
+        for l in range(cfg.num_layers):
+            lw = layer0 if l == 0 else W.layer_weights(cfg, l)
+            if keep_inputs:
+                kept_layers.append(lw)
+            yield lw
+
+    enc = B.EpdEncoder(cfg, gw, layer_stream(), max_tokens=T, max_segments=len(cu) - 1, max_items=len(grids))
+    log("[bench] inputs generated and uploaded in %.1f s; workspace %.2f GB" % (time.perf_counter() - t0, enc.workspace_bytes / 1e9))
     p_dev = B.to_device_patches(patches, cfg.dtype)
     out = torch.empty((Tm, cfg.out_dim), dtype=B.torch_dtype(cfg.dtype), device="cuda:0")
-    log("[bench] workspace %.2f GB" % (enc.workspace_bytes / 1e9))
 
-    # ---- warm-up, with a per-step timing pass to find the dominant kernel
-    for _ in range(max(1, args.warmup)):
+    # ---- warm-up, then one call per step with HIP events around each launch of that step
+    for _ in range(max(1, warmup)):
         enc.encode(p_dev, cu, grid, out)
     torch.cuda.synchronize()
     table = {}
@@ -190,41 +173,51 @@ def main():
         enc.set_timing(step)
         enc.encode(p_dev, cu, grid, out)
         torch.cuda.synchronize()
-        ms, n, work = enc.get_timing()
-        table[B.STEP_NAMES[step]] = (ms, n, work)
+        table[B.STEP_NAMES[step]] = enc.get_timing()
     enc.set_timing(-1)
     tot = sum(v[0] for v in table.values())
     log("[bench] per-step kernel time of one call (HIP events around each launch):")
+    steps_roof = {}
     for k, (ms, n, work) in table.items():
-        if n == 0:
+        if n == 0 or k == "plan":
             continue
         rate = work / (ms * 1e-3) if ms > 0 else 0.0
-        unit = "GB/s" if k == "norm" else "TFLOP/s"
-        scale = 1e9 if k == "norm" else 1e12
-        log("    %-12s %4d launches %9.3f ms  %5.1f%%  %8.1f %s" % (k, n, ms, 100 * ms / tot, rate / scale, unit))
-    mat_steps = [k for k in table if k not in ("plan", "norm") and table[k][1] > 0]
+        hbm = k == "norm"
+        peak = PEAK_HBM_GBS if hbm else PEAK_BF16_TFLOPS
+        ach = rate / (1e9 if hbm else 1e12)
+        steps_roof[k] = {"bound": "hbm" if hbm else "mfma", "achieved": ach, "peak": peak, "unit": "GB/s" if hbm else "TFLOP/s",
+                         "frac": ach / peak, "launches": n, "avg_launch_ms": ms / n,
+                         ("bytes_per_launch" if hbm else "flops_per_launch"): work / n}
+        log("    %-12s %4d launches %9.3f ms  %5.1f%%  %8.1f %s  (%.1f%% of peak)" % (k, n, ms, 100 * ms / tot, ach, steps_roof[k]["unit"], 100 * ach / peak))
+    if "merge" in steps_roof:
+        # the merger's A operand is a 2x2 gather of the normalised rows: bytes it has to move at least
+        # (gathered rows once, weights once, output once) over the kernel's time
+        es = 2 if cfg.dtype == "bf16" else 4
+        gbytes = (Tm * cfg.merge ** 2 * cfg.hidden + cfg.out_dim * cfg.merge ** 2 * cfg.hidden + Tm * cfg.out_dim) * es
+        steps_roof["merge"]["gather_algorithmic_GBs"] = gbytes / (table["merge"][0] * 1e-3) / 1e9
+    mat_steps = [k for k in steps_roof if k != "norm"]
     dom = max(mat_steps, key=lambda k: table[k][0])
     dom_id = B.STEP_NAMES.index(dom)
 
-    # ---- timed region: exactly K steps; the dominant kernel is bracketed by HIP events
-    # --in-flight N > 1: N encoders (own workspace and output each) on N streams of default
-    # priority take the steps in turn, so that kernels of different batches fill each other's
-    # idle compute units; the default, 1, is the plain sequence of calls on one stream
+    # ---- timed region: exactly `steps` calls; the dominant kernel is bracketed by HIP events.
+    # in_flight N > 1: N encoders (own workspace and output each) on N streams of default priority
+    # take the steps in turn, so that kernels of different batches fill each other's idle compute
+    # units; the default, 1, is the plain sequence of calls on one stream
     extra = []
-    if args.in_flight > 1:
-        for _ in range(args.in_flight - 1):
-            extra.append((B.EpdEncoder(cfg, gw, layers, max_tokens=T, max_segments=len(cu) - 1, max_items=len(grids)),
+    if in_flight > 1:
+        for _ in range(in_flight - 1):
+            extra.append((B.EpdEncoder(cfg, gw, (layer0 if l == 0 else W.layer_weights(cfg, l) for l in range(cfg.num_layers)),
+                                       max_tokens=T, max_segments=len(cu) - 1, max_items=len(grids)),
                           torch.empty_like(out), torch.cuda.Stream()))
         for e, o, st in extra:
             with torch.cuda.stream(st):
                 e.encode(p_dev, cu, grid, o)
         torch.cuda.synchronize()
-    # with several lanes none of them is the default stream (whose launches order against the others')
     lanes = [(enc, out, torch.cuda.Stream() if extra else torch.cuda.current_stream())] + extra
     enc.set_timing(dom_id)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         e, o, st = lanes[i % len(lanes)]
         with torch.cuda.stream(st):
             e.encode(p_dev, cu, grid, o)
@@ -237,114 +230,191 @@ def main():
         for e, _, _ in extra:
             e.close()
 
-    ms_per_step = dt / args.steps * 1e3
-    value = Tm * args.steps / dt
-    achieved = dom_work / (dom_ms * 1e-3) / 1e12          # TFLOP/s over the kernel's own time
-    D, F, L = cfg.hidden, cfg.mlp_dim, cfg.num_layers
-    flops_call = (2.0 * T * cfg.patch_dim * D + L * (8.0 * T * D * D + 4.0 * T * D * F)
-                  + L * sum(4.0 * float(cu[i + 1] - cu[i]) ** 2 * D for i in range(len(cu) - 1))
-                  + 2.0 * Tm * (cfg.merge ** 2 * D) * cfg.out_dim)
-    log("[bench] %.3f ms/step, %.0f visual tokens/s, %.1f TFLOP/s end to end (%.1f%% of bf16 peak)"
-        % (ms_per_step, value, flops_call / (ms_per_step * 1e-3) / 1e12,
-           100 * flops_call / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS))
-
-    # ---- the step in front of the path (raw uint8 pixels -> packed patch rows), timed on its
-    # own: it is not part of `value`, whose inputs are the packed rows already in HBM
-    prep = None
-    store_res = None
-    if cfg.patch % 2 == 0:
-        src = [(int(h) * cfg.patch, int(w) * cfg.patch) for _, h, w in grids]
-        px = torch.from_numpy(np.concatenate([W.item_pixels_u8(cfg, i, g, s).ravel()
-                                              for i, (g, s) in enumerate(zip(grids, src))])).to("cuda:0")
-        rows = torch.empty_like(p_dev)
-        mean, std = [0.5] * cfg.in_channels, [0.25] * cfg.in_channels
-        for _ in range(3):
-            enc.preprocess(px, src, grids, mean, std, out=rows)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 50
-        # a few milliseconds of unrelated GPU work go first, so that the host has queued all the
-        # launches by the time the first one runs and the events bracket kernel time only
-        blocker = torch.ones((8192, 8192), dtype=torch.bfloat16, device="cuda:0")
-        torch.cuda.synchronize()
-        for _ in range(8):
-            blocker @ blocker
-        e0.record()
-        for _ in range(reps):
-            enc.preprocess(px, src, grids, mean, std, out=rows)
-        e1.record()
-        torch.cuda.synchronize()
-        del blocker
-        p_ms = e0.elapsed_time(e1) / reps
-        p_bytes = px.numel() + rows.numel() * rows.element_size()
-        prep = {"ms": p_ms, "bytes": p_bytes, "achieved_GBs": p_bytes / (p_ms * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
-                "frac": p_bytes / (p_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bound": "hbm",
-                "note": "epd_preprocess, sources at grid size (no resize); mean of %d launches queued back to back" % reps}
-        log("[bench] epd_preprocess: %.4f ms per call, %.1f MB -> %.0f GB/s" % (p_ms, p_bytes / 1e6, prep["achieved_GBs"]))
-        # ---- the step behind it: the feature store (hash of the input as key; a hit skips the encoder)
-        if args.config == "C2" and args.layers is None:
-            store = B.MMStore((1 << 20) + 2 * out.numel() * out.element_size())
-            offs = np.concatenate([[0], np.cumsum([cfg.in_channels * t * cfg.temporal_patch * hs * ws
-                                                   for (t, _, _), (hs, ws) in zip(grids, src)])]).astype(np.uint64)
-            for _ in range(2):
-                store.hash(px, offs, [1] * len(grids))
-            t0 = time.perf_counter()
-            for _ in range(20):
-                store.hash(px, offs, [1] * len(grids))
-            h_ms = (time.perf_counter() - t0) / 20 * 1e3           # includes the wait for the 128 bytes of keys
-            t0 = time.perf_counter()
-            _, hit_a, _ = enc.encode_cached(store, 7, px, src, grids, mean, std)
-            torch.cuda.synchronize()
-            miss_ms = (time.perf_counter() - t0) * 1e3
-            t0 = time.perf_counter()
-            for _ in range(10):
-                _, hit_b, _ = enc.encode_cached(store, 7, px, src, grids, mean, std)
-            torch.cuda.synchronize()
-            hit_ms = (time.perf_counter() - t0) / 10 * 1e3
-            assert not hit_a.any() and hit_b.all()
-            store_res = {"hash_ms_per_call_incl_sync": h_ms, "hash_bytes": int(px.numel()),
-                         "all_miss_call_ms": miss_ms, "all_hit_call_ms": hit_ms,
-                         "note": "epd_store_hash of the 8 images (one launch pair + key copy + wait); "
-                                 "epd_encode_cached on raw pixels: first call (preprocess + encode + file) vs repeated call"}
-            log("[bench] mm store: hash %.3f ms per call (%.1f MB, waits for the keys); encode_cached all-miss %.3f ms, all-hit %.3f ms"
-                % (h_ms, px.numel() / 1e6, miss_ms, hit_ms))
-            store.close()
-        del px, rows
-
-    gpu_out = out.float().cpu().numpy()
-    cpu = None
-    if args.cpu_items > 0:
-        cpu = cpu_baseline(cfg, gw, layers, patches, cu, grid, gpu_out, min(args.cpu_items, len(grids)))
-
-    # HBM-side bytes per launch of the dominant kernel come from rocprofv3 --pmc FETCH_SIZE /
-    # WRITE_SIZE runs of this same command (see profiles/); they cannot be collected in-process.
-    traffic = None
-    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "c2_bench_hbm_traffic.txt")
-    if args.config == "C2" and args.layers is None and os.path.exists(tfile):
-        for line in open(tfile):
-            parts = line.split()
-            if len(parts) >= 3 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == dom:
-                traffic = float(parts[2])
+    ms_per_step = dt / steps * 1e3
+    fl, fl_attn = flops_per_call(cfg, T, Tm, cu)
+    tfl = fl / (ms_per_step * 1e-3) / 1e12
+    achieved = dom_work / (dom_ms * 1e-3) / 1e12
+    log("[bench] %s: %.3f ms/step, %.0f visual tokens/s, %.1f TFLOP/s end to end (%.1f%% of bf16 peak); dominant kernel %s at %.1f TFLOP/s"
+        % (cfg.name, ms_per_step, Tm * steps / dt, tfl, 100 * tfl / PEAK_BF16_TFLOPS, dom, achieved))
+    traffic, traffic_src = (None, "depth or segments differ from the profiled run") if (layers_override is not None or segments != "item" or in_flight != 1) \
+        else stored_traffic(name, dom)
     res = {
-        "metric": "visual tokens/sec (ViT encode fwd, 1 GPU) + MFMA util % of bf16 peak",
-        "value": value, "unit": "visual tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": "%s: %d layers, D=%d, %dx%d heads, MLP %d, patch %d, %d items, %d patch tokens -> %d visual tokens"
-                               % (cfg.name, L, D, cfg.num_heads, cfg.head_dim, F, cfg.patch, len(grids), T, Tm),
-                   "batches_in_flight": args.in_flight, "patch_tokens": T, "visual_tokens": Tm, "patch_tokens_per_s": T * args.steps / dt,
-                   "tflops_end_to_end": flops_call / (ms_per_step * 1e-3) / 1e12,
-                   "mfma_util_pct_end_to_end": 100 * flops_call / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "name": name, "cfg": cfg, "grids": grids, "cu": cu, "grid": grid, "T": T, "Tm": Tm,
+        "value": Tm * steps / dt, "ms_per_step": ms_per_step, "seconds": dt, "tflops": tfl, "flops_per_call": fl,
+        "attention_flop_share": fl_attn / fl,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
-                     "launches": dom_n, "avg_launch_ms": dom_ms / max(dom_n, 1),
-                     "flops_per_launch": dom_work / max(dom_n, 1)},
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
+                     "launches": dom_n, "avg_launch_ms": dom_ms / max(dom_n, 1), "flops_per_launch": dom_work / max(dom_n, 1)},
+        "rooflines_per_step": steps_roof,
+        "steps_ms": {k: v[0] for k, v in table.items() if v[1] > 0},
+        "workload": "%s: %d layers, D=%d, %dx%d heads, MLP %d, patch %d x temporal %d, %d items, %d attention segments, %d patch tokens -> %d visual tokens"
+                    % (cfg.name, cfg.num_layers, cfg.hidden, cfg.num_heads, cfg.head_dim, cfg.mlp_dim, cfg.patch, cfg.temporal_patch,
+                       len(grids), len(cu) - 1, T, Tm),
+        "enc": enc, "p_dev": p_dev, "out": out, "gw": gw, "layer0": layer0, "layers": kept_layers, "patches": patches,
+    }
+    return res
+
+
+def release(res):
+    import torch
+    res["enc"].close()
+    for k in ("enc", "p_dev", "out", "gw", "layer0", "layers", "patches"):
+        res.pop(k, None)
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def summary_block(res):
+    return {"workload": res["workload"], "value": res["value"], "unit": "visual tokens/s", "ms_per_step": res["ms_per_step"],
+            "patch_tokens_per_s": res["T"] / (res["ms_per_step"] * 1e-3), "tflops_end_to_end": res["tflops"],
+            "mfma_util_pct_end_to_end": 100 * res["tflops"] / PEAK_BF16_TFLOPS, "attention_flop_share": res["attention_flop_share"],
+            "roofline": res["roofline"], "rooflines_per_step": res["rooflines_per_step"], "steps_ms": res["steps_ms"]}
+
+
+def preprocess_and_store(res, with_store):
+    """The step in front of the path (raw uint8 pixels -> packed patch rows) and the one behind it
+    (feature store), timed on their own: neither is part of `value`, whose inputs are the packed
+    rows already in HBM."""
+    import torch
+    from paper_2601_11590_amd import binding as B, workloads as W
+    cfg, grids, enc, p_dev, out = res["cfg"], res["grids"], res["enc"], res["p_dev"], res["out"]
+    if cfg.patch % 2:
+        return None, None
+    src = [(int(h) * cfg.patch, int(w) * cfg.patch) for _, h, w in grids]
+    px = torch.from_numpy(np.concatenate([W.item_pixels_u8(cfg, i, g, s).ravel() for i, (g, s) in enumerate(zip(grids, src))])).to("cuda:0")
+    rows = torch.empty_like(p_dev)
+    mean, std = [0.5] * cfg.in_channels, [0.25] * cfg.in_channels
+    for _ in range(3):
+        enc.preprocess(px, src, grids, mean, std, out=rows)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 50
+    # a few milliseconds of unrelated GPU work go first, so that the host has queued all the
+    # launches by the time the first one runs and the events bracket kernel time only
+    blocker = torch.ones((8192, 8192), dtype=torch.bfloat16, device="cuda:0")
+    torch.cuda.synchronize()
+    for _ in range(8):
+        blocker @ blocker
+    e0.record()
+    for _ in range(reps):
+        enc.preprocess(px, src, grids, mean, std, out=rows)
+    e1.record()
+    torch.cuda.synchronize()
+    del blocker
+    p_ms = e0.elapsed_time(e1) / reps
+    p_bytes = px.numel() + rows.numel() * rows.element_size()
+    prep = {"ms": p_ms, "bytes": p_bytes, "achieved_GBs": p_bytes / (p_ms * 1e-3) / 1e9, "peak_GBs": PEAK_HBM_GBS,
+            "frac": p_bytes / (p_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bound": "hbm",
+            "note": "epd_preprocess, sources at grid size (no resize); mean of %d launches queued back to back" % reps}
+    log("[bench] epd_preprocess: %.4f ms per call, %.1f MB -> %.0f GB/s" % (p_ms, p_bytes / 1e6, prep["achieved_GBs"]))
+    store_res = None
+    if with_store:
+        store = B.MMStore((1 << 20) + 2 * out.numel() * out.element_size())
+        offs = np.concatenate([[0], np.cumsum([cfg.in_channels * t * cfg.temporal_patch * hs * ws
+                                               for (t, _, _), (hs, ws) in zip(grids, src)])]).astype(np.uint64)
+        for _ in range(2):
+            store.hash(px, offs, [1] * len(grids))
+        t0 = time.perf_counter()
+        for _ in range(20):
+            store.hash(px, offs, [1] * len(grids))
+        h_ms = (time.perf_counter() - t0) / 20 * 1e3           # includes the wait for the keys
+        t0 = time.perf_counter()
+        _, hit_a, _ = enc.encode_cached(store, 7, px, src, grids, mean, std)
+        torch.cuda.synchronize()
+        miss_ms = (time.perf_counter() - t0) * 1e3
+        t0 = time.perf_counter()
+        for _ in range(10):
+            _, hit_b, _ = enc.encode_cached(store, 7, px, src, grids, mean, std)
+        torch.cuda.synchronize()
+        hit_ms = (time.perf_counter() - t0) / 10 * 1e3
+        assert not hit_a.any() and hit_b.all()
+        store_res = {"hash_ms_per_call_incl_sync": h_ms, "hash_bytes": int(px.numel()),
+                     "all_miss_call_ms": miss_ms, "all_hit_call_ms": hit_ms,
+                     "note": "epd_store_hash of the items (one launch pair + key copy + wait); "
+                             "epd_encode_cached on raw pixels: first call (preprocess + encode + file) vs repeated call"}
+        log("[bench] mm store: hash %.3f ms per call (%.1f MB, waits for the keys); encode_cached all-miss %.3f ms, all-hit %.3f ms"
+            % (h_ms, px.numel() / 1e6, miss_ms, hit_ms))
+        store.close()
+    return prep, store_res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C5", help="headline workload: C5 (default, the largest single-GPU configuration) | C2 | C3 | C4")
+    ap.add_argument("--others", default=None,
+                    help="comma-separated configurations timed briefly beside the headline (default: C2,C3,C4 with C5, none otherwise; '' = none)")
+    ap.add_argument("--layers", type=int, default=None, help="override depth (experiments only; never the headline)")
+    ap.add_argument("--segments", default="item", choices=["item", "frame"],
+                    help="attention segments: one per image / clip (default) or one per video frame (windowed attention)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--in-flight", type=int, default=1,
+                    help="batches in flight on separate streams (serving mode; default 1 = one stream)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+            "--gpus %d is not supported. Items would shard across GPUs by image with replicated "
+            "weights; nothing here launches more than one rank." % args.gpus)
+        sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("[bench] copied 5 x 1 GiB (reads 1 GiB and writes 1 GiB per launch)")
+        return
+
+    plain = args.layers is None and args.segments == "item" and args.in_flight == 1
+    small = args.config in ("C2", "C3")           # the oracle runs these at full depth in seconds
+    head = measure(args.config, args.steps, args.warmup, args.in_flight, args.layers, args.segments, keep_inputs=small and not args.no_cpu)
+    prep, store_res = preprocess_and_store(head, with_store=args.config == "C2" and plain)
+    gpu_out = head["out"].float().cpu().numpy()
+    stored = stored_rows_parity(args.config, gpu_out) if plain else None
+    cpu = None
+    if not args.no_cpu:
+        if small:
+            n = len(head["grids"]) if args.config == "C2" else 3
+            cpu = cpu_baseline_full(head["cfg"], head["gw"], head["layers"], head["patches"], head["grid"], gpu_out, n) if args.segments == "item" else None
+        elif head["cfg"].num_layers > 0:
+            cpu = cpu_baseline_depth_sample(head["cfg"], head["gw"], head["layer0"], head["patches"], head["grid"])
+    cfg = head["cfg"]
+    line = {
+        "metric": "visual tokens/sec (ViT encode fwd, 1 GPU) + MFMA util % of bf16 peak",
+        "value": head["value"], "unit": "visual tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": head["workload"], "batches_in_flight": args.in_flight, "patch_tokens": head["T"], "visual_tokens": head["Tm"],
+                   "patch_tokens_per_s": head["T"] / (head["ms_per_step"] * 1e-3), "tflops_end_to_end": head["tflops"],
+                   "mfma_util_pct_end_to_end": 100 * head["tflops"] / PEAK_BF16_TFLOPS,
+                   "attention_flop_share": head["attention_flop_share"]},
+        "roofline": head["roofline"],
+        "rooflines_per_step": head["rooflines_per_step"],
         "cpu_baseline": cpu,
+        "parity_vs_stored_oracle_rows": stored,
         "preprocess": prep,
         "mm_store": store_res,
-        "steps_ms": {k: v[0] for k, v in table.items() if v[1] > 0},
+        "steps_ms": head["steps_ms"],
+        "peaks": {"bf16_mfma_TFLOPs": PEAK_BF16_TFLOPS, "hbm_GBs": PEAK_HBM_GBS},
     }
-    enc.close()
-    print(json.dumps(res), flush=True)
+    release(head)
+    others = args.others
+    if others is None:
+        others = "C2,C3,C4" if (args.config == "C5" and plain) else ""
+    blocks = {}
+    for name in [n for n in others.split(",") if n]:
+        r = measure(name, 5, 2)
+        blocks[name] = summary_block(r)
+        if name in ("C4",):
+            blocks[name]["parity_vs_stored_oracle_rows"] = stored_rows_parity(name, r["out"].float().cpu().numpy())
+        release(r)
+    line["others"] = blocks
+    print(json.dumps(line), flush=True)
 
 
 if __name__ == "__main__":
