@@ -200,6 +200,25 @@ const char* epd_store_last_error(epd_store_handle s);
 epd_status epd_store_hash(epd_store_handle s, const void* device_data, const uint64_t* offsets,
                           const uint64_t* salts, int32_t n, uint64_t* keys_out, void* stream);
 
+/* For callers that cannot allocate device memory or wait for the GPU -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: the keys of epd_store_hash (bit
+ * for bit), with no store, no pool and no host synchronisation.
+ *   device_data      device: the buffer the ranges lie in
+ *   offsets, salts   HOST uint64 [n + 1] / [n], as for epd_store_hash; consumed before the call returns
+ *   n                1 .. 32 ranges per call; more returns EPD_ERR_SHAPE with nothing launched
+ *   keys_device_out  DEVICE uint64 [n, 2]: written by the second of the two kernels this call
+ *                    enqueues on `stream`; valid once the stream has passed that kernel
+ * The partial hashes live in a 512 KiB array the library holds statically on every GPU it is
+ * loaded on (one copy per GPU, for the life of the process): the call allocates and frees nothing,
+ * copies nothing and waits for nothing.  All calls on one GPU share that array, so two calls whose
+ * kernels may overlap on the same GPU (different streams) race: order them.  Calls on different
+ * GPUs are independent.  Errors: EPD_ERR_INVALID_ARG (NULL pointer, n <= 0), EPD_ERR_SHAPE (n > 32,
+ * decreasing offsets, a range of 8 GiB or more), EPD_ERR_HIP; message from
+ * epd_store_last_error(NULL). */
+epd_status epd_store_hash_noalloc(const void* device_data, const uint64_t* offsets,
+                                  const uint64_t* salts, int32_t n, uint64_t* keys_device_out,
+                                  void* stream);
+
 /* EPD_OK: *device_ptr / *bytes describe the stored value (valid until a later insert drops
  * it); EPD_MISS: not stored.  `bytes` may be NULL. */
 epd_status epd_store_lookup(epd_store_handle s, const uint64_t key[2], void** device_ptr,

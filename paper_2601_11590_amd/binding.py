@@ -58,7 +58,7 @@ class epd_encode_cfg(C.Structure):
 EXPORTS = ["epd_encode_workspace_bytes", "epd_encode_create", "epd_encode", "epd_encode_destroy",
            "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing", "epd_encode_set_tuning",
            "epd_encode_get_timing", "epd_preprocess", "epd_encode_cached", "epd_store_create",
-           "epd_store_destroy", "epd_store_last_error", "epd_store_hash", "epd_store_lookup", "epd_store_insert",
+           "epd_store_destroy", "epd_store_last_error", "epd_store_hash", "epd_store_hash_noalloc", "epd_store_lookup", "epd_store_insert",
            "epd_store_stats"]
 
 
@@ -82,6 +82,8 @@ def _load() -> C.CDLL:
     lib.epd_store_last_error.argtypes = [C.c_void_p]
     lib.epd_store_hash.restype = C.c_int
     lib.epd_store_hash.argtypes = [C.c_void_p, C.c_void_p, U64P, U64P, C.c_int32, U64P, C.c_void_p]
+    lib.epd_store_hash_noalloc.restype = C.c_int
+    lib.epd_store_hash_noalloc.argtypes = [C.c_void_p, U64P, U64P, C.c_int32, C.c_void_p, C.c_void_p]
     lib.epd_store_lookup.restype = C.c_int
     lib.epd_store_lookup.argtypes = [C.c_void_p, U64P, C.POINTER(C.c_void_p), U64P]
     lib.epd_store_insert.restype = C.c_int
@@ -225,6 +227,17 @@ def epd_store_hash(store, data_ptr: int, offsets, salts, stream: int) -> np.ndar
     if st != EPD_OK:
         raise StoreError(st, epd_store_last_error(store))
     return keys
+
+
+def epd_store_hash_noalloc(data_ptr: int, offsets, salts, keys_device_ptr: int, stream: int) -> None:
+    """Keys of the byte ranges into a device buffer uint64 [n, 2]; enqueues only (no wait)."""
+    off = np.ascontiguousarray(offsets, dtype=np.uint64)
+    sa = np.ascontiguousarray(salts, dtype=np.uint64)
+    assert len(off) == len(sa) + 1
+    U64P = C.POINTER(C.c_uint64)
+    st = lib.epd_store_hash_noalloc(data_ptr, off.ctypes.data_as(U64P), sa.ctypes.data_as(U64P), len(sa), keys_device_ptr, stream)
+    if st != EPD_OK:
+        raise StoreError(st, epd_store_last_error(None))
 
 
 def epd_encode_cached(handle, store, model_salt: int, pixels: int, src_hw, grid_thw, mean, std, rows_scratch: int,

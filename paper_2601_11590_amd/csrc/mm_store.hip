@@ -23,6 +23,7 @@
 #include <cstdio>
 #include <list>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -169,6 +170,17 @@ __global__ __launch_bounds__(kThreads) void hash_final_kernel(HashArgs a) {
   }
 }
 
+// Partial-hash scratch of epd_store_hash_noalloc: one slot pair per (range, block) of one launch.
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress -- it is not a
+// device address and never goes into a kernel argument or a copy.
+constexpr size_t kStaticScratchWords = (size_t)kRanges * kMaxBlocks * 2;
+static __device__ __align__(256) uint64_t scratch[kStaticScratchWords];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint64_t* g_scratch_ptr[kMaxDevices] = {};     // device address of `scratch` on each device, once known
+
 }  // namespace
 
 struct epd_store {
@@ -277,16 +289,46 @@ epd_status epd_store_stats(epd_store_handle s, uint64_t* hits, uint64_t* misses,
   return EPD_OK;
 }
 
+// Describes ranges [i0, i0 + m) in `a` and launches the two hash kernels for them: partial hashes
+// go to a.partial, the m keys to a.result (both set by the caller).
+static void launch_hash(HashArgs& a, const void* device_data, const uint64_t* offsets, const uint64_t* salts, int i0, int m,
+                        hipStream_t st) {
+  uint32_t max_blocks = 1;
+  for (int j = 0; j < m; ++j) {
+    HashRange& r = a.r[j];
+    r.data = (const uint8_t*)device_data + offsets[i0 + j];
+    r.bytes = offsets[i0 + j + 1] - offsets[i0 + j];
+    r.salt = salts[i0 + j];
+    r.words = (uint32_t)((r.bytes + 3) / 4);
+    const uint64_t per_thread = ((uint64_t)r.words + (uint64_t)kMaxBlocks * kThreads - 1) / ((uint64_t)kMaxBlocks * kThreads);
+    r.words_per_thread = (uint32_t)((per_thread + kMinWords - 1) / kMinWords * kMinWords);
+    if (r.words_per_thread == 0) r.words_per_thread = kMinWords;
+    const uint64_t per_block = (uint64_t)r.words_per_thread * kThreads;
+    r.blocks = (uint32_t)(((uint64_t)r.words + per_block - 1) / per_block);
+    if (r.blocks == 0) r.blocks = 1;
+    if (r.blocks > max_blocks) max_blocks = r.blocks;
+  }
+  a.n = m;
+  hipLaunchKernelGGL(hash_partial_kernel, dim3(max_blocks, m), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL(hash_final_kernel, dim3(m), dim3(kThreads), 0, st, a);
+}
+
+static bool ranges_ok(const uint64_t* offsets, int n, std::string& err) {
+  for (int i = 0; i < n; ++i)
+    if (offsets[i + 1] < offsets[i] || offsets[i + 1] - offsets[i] >= (1ull << 33)) {
+      err = fmt("range %d: offsets must not decrease and a range holds less than 8 GiB", i);
+      return false;
+    }
+  return true;
+}
+
 epd_status epd_store_hash(epd_store_handle s, const void* device_data, const uint64_t* offsets, const uint64_t* salts,
                           int32_t n, uint64_t* keys_out, void* stream) {
   if (!s) { g_store_error = "store is NULL"; return EPD_ERR_INVALID_ARG; }
   if (!device_data || !offsets || !salts || !keys_out || n <= 0) {
     s->err = "a required pointer is NULL or n <= 0"; return EPD_ERR_INVALID_ARG;
   }
-  for (int i = 0; i < n; ++i)
-    if (offsets[i + 1] < offsets[i] || offsets[i + 1] - offsets[i] >= (1ull << 33)) {
-      s->err = fmt("range %d: offsets must not decrease and a range holds less than 8 GiB", i); return EPD_ERR_SHAPE;
-    }
+  if (!ranges_ok(offsets, n, s->err)) return EPD_ERR_SHAPE;
   hipStream_t st = (hipStream_t)stream;
   HashArgs a{};
   a.partial = (uint64_t*)s->pool;
@@ -294,28 +336,55 @@ epd_status epd_store_hash(epd_store_handle s, const void* device_data, const uin
   static_assert(((size_t)kRanges * kMaxBlocks * 2 + kRanges * 2) * 8 <= kScratchBytes, "hash scratch");
   for (int i0 = 0; i0 < n; i0 += kRanges) {
     const int m = n - i0 < kRanges ? n - i0 : kRanges;
-    uint32_t max_blocks = 1;
-    for (int j = 0; j < m; ++j) {
-      HashRange& r = a.r[j];
-      r.data = (const uint8_t*)device_data + offsets[i0 + j];
-      r.bytes = offsets[i0 + j + 1] - offsets[i0 + j];
-      r.salt = salts[i0 + j];
-      r.words = (uint32_t)((r.bytes + 3) / 4);
-      const uint64_t per_thread = ((uint64_t)r.words + (uint64_t)kMaxBlocks * kThreads - 1) / ((uint64_t)kMaxBlocks * kThreads);
-      r.words_per_thread = (uint32_t)((per_thread + kMinWords - 1) / kMinWords * kMinWords);
-      if (r.words_per_thread == 0) r.words_per_thread = kMinWords;
-      const uint64_t per_block = (uint64_t)r.words_per_thread * kThreads;
-      r.blocks = (uint32_t)(((uint64_t)r.words + per_block - 1) / per_block);
-      if (r.blocks == 0) r.blocks = 1;
-      if (r.blocks > max_blocks) max_blocks = r.blocks;
-    }
-    a.n = m;
-    hipLaunchKernelGGL(hash_partial_kernel, dim3(max_blocks, m), dim3(kThreads), 0, st, a);
-    hipLaunchKernelGGL(hash_final_kernel, dim3(m), dim3(kThreads), 0, st, a);
+    launch_hash(a, device_data, offsets, salts, i0, m, st);
     hipError_t e = hipMemcpyAsync(keys_out + (size_t)i0 * 2, a.result, (size_t)m * 16, hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);      // the keys decide what is launched next
     if (e != hipSuccess) { s->err = fmt("hash launch or copy failed: %s", hipGetErrorString(e)); return EPD_ERR_HIP; }
   }
+  return EPD_OK;
+}
+
+// The same keys for callers that cannot allocate: the partial hashes go to the library's own
+// static device array instead of a pool, the keys to a device buffer of the caller, and the host
+// is not waited for.  Nothing here allocates or frees memory (device or pinned), copies, or
+// synchronises; the two launches are all the GPU work.
+epd_status epd_store_hash_noalloc(const void* device_data, const uint64_t* offsets, const uint64_t* salts, int32_t n,
+                                  uint64_t* keys_device_out, void* stream) {
+  if (!device_data || !offsets || !salts || !keys_device_out || n <= 0) {
+    g_store_error = "a required pointer is NULL or n <= 0"; return EPD_ERR_INVALID_ARG;
+  }
+  if (n > kRanges) {
+    g_store_error = fmt("%d ranges: one call of epd_store_hash_noalloc takes at most %d (its scratch array holds that many)", n, kRanges);
+    return EPD_ERR_SHAPE;
+  }
+  if (!ranges_ok(offsets, n, g_store_error)) return EPD_ERR_SHAPE;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    g_store_error = fmt("no usable current device (%s, device %d)", hipGetErrorString(e), dev); return EPD_ERR_HIP;
+  }
+  uint64_t* ptr;
+  {
+    // first call on this device: ask the runtime where this device keeps its copy of the array
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) {
+        g_store_error = fmt("hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e)); return EPD_ERR_HIP;
+      }
+      g_scratch_ptr[dev] = (uint64_t*)p;
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  // Nothing in the array has to start at zero: the first kernel writes the slot of every block the
+  // second one reads, so the previous call's contents are simply overwritten.
+  HashArgs a{};
+  a.partial = ptr;
+  a.result = keys_device_out;
+  launch_hash(a, device_data, offsets, salts, 0, n, (hipStream_t)stream);
+  e = hipGetLastError();
+  if (e != hipSuccess) { g_store_error = fmt("hash launch failed: %s", hipGetErrorString(e)); return EPD_ERR_HIP; }
   return EPD_OK;
 }
 
