@@ -71,28 +71,34 @@ def cpu_baseline_full(cfg, gw, layers, patches, grid, gpu_out, n_items):
 
 
 def cpu_baseline_depth_sample(cfg, gw, layer0, patches, grid):
-    """The CPU oracle, as it stands, on the first item of the batch with 0 and with 1 of the
-    configuration's layers (a full-depth run takes the oracle tens of minutes); the rate at
-    full depth is the linear extrapolation in depth, every layer having the same shape."""
+    """The CPU oracle, as it stands, on one item of the batch (the largest of at most 12 288
+    tokens, else the smallest) with 0 and with 1 of the configuration's layers (a full-depth run
+    takes the oracle tens of minutes); the rate at full depth is the linear extrapolation in
+    depth, every layer having the same shape."""
     from oracle import vit_encode as O
     from paper_2601_11590_amd import workloads as W
-    g0 = [tuple(int(v) for v in grid[0])]
+    toks = [int(t) * int(h) * int(w) for t, h, w in grid]
+    fits = [i for i, n in enumerate(toks) if n <= 12288]
+    item = max(fits, key=lambda i: toks[i]) if fits else int(np.argmin(toks))
+    g0 = [tuple(int(v) for v in grid[item])]
     T, Tm = W.num_tokens(g0), W.num_merged_tokens(g0, cfg.merge)
+    first = sum(toks[:item])
+    rows = patches[first:first + T]
     cu1, g1 = W.metadata(g0)
     t = time.perf_counter()
-    O.encode(cfg.replace(num_layers=0), gw, [], patches[:T], cu1, g1)
+    O.encode(cfg.replace(num_layers=0), gw, [], rows, cu1, g1)
     t_l0 = time.perf_counter() - t
     t = time.perf_counter()
-    O.encode(cfg.replace(num_layers=1), gw, [layer0], patches[:T], cu1, g1)
+    O.encode(cfg.replace(num_layers=1), gw, [layer0], rows, cu1, g1)
     t_l1 = time.perf_counter() - t
     per_layer = max(t_l1 - t_l0, 1e-9)
     full = t_l0 + cfg.num_layers * per_layer
-    log("[bench] oracle on item 0 (%d tokens): %.2f s with 0 layers, %.2f s with 1 layer -> %.0f s extrapolated to %d layers"
-        % (T, t_l0, t_l1, full, cfg.num_layers))
+    log("[bench] oracle on item %d (%d tokens): %.2f s with 0 layers, %.2f s with 1 layer -> %.0f s extrapolated to %d layers"
+        % (item, T, t_l0, t_l1, full, cfg.num_layers))
     return {"value": Tm / full, "unit": "visual tokens/s", "cores": host_cores(), "kind": "oracle",
-            "sample": "item 0 of %d (%d patch tokens -> %d visual tokens): the oracle timed once with 0 layers (%.2f s) and once "
+            "sample": "item %d of %d (%d patch tokens -> %d visual tokens): the oracle timed once with 0 layers (%.2f s) and once "
                       "with 1 layer (%.2f s) of the %d; value = %d / (t0 + %d (t1 - t0)), a linear extrapolation in depth "
-                      "(all layers have one shape), fp64 NumPy" % (len(grid), T, Tm, t_l0, t_l1, cfg.num_layers, Tm, cfg.num_layers),
+                      "(all layers have one shape), fp64 NumPy" % (item, len(grid), T, Tm, t_l0, t_l1, cfg.num_layers, Tm, cfg.num_layers),
             "seconds": t_l0 + t_l1, "extrapolated_full_depth_seconds": full}
 
 
@@ -342,7 +348,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="C5", help="headline workload: C5 (default, the largest single-GPU configuration) | C2 | C3 | C4")
+    ap.add_argument("--config", default="C5", help="headline workload: C5 (default, the largest single-GPU configuration) | C2 | C3 | C4 | "
+                         "T42 (the six image resolutions of the paper's Table 4_2 as one batch)")
     ap.add_argument("--others", default=None,
                     help="comma-separated configurations timed briefly beside the headline (default: C2,C3,C4 with C5, none otherwise; '' = none)")
     ap.add_argument("--layers", type=int, default=None, help="override depth (experiments only; never the headline)")

@@ -75,6 +75,25 @@ C5 = EncoderConfig(name="C5-video-6B-bf16", dtype="bf16", num_layers=45, hidden=
                    num_heads=25, head_dim=128, mlp_dim=12800, patch=14, temporal_patch=2,
                    norm="rmsnorm", rope="3d", rope_pairs=(16, 24, 24), out_dim=8192, seed=0)
 
+# The six image resolutions of the paper's Table 4_2 (section 4.2; the table prints the encoder
+# output as [n, 3584] per resolution), pixels as printed.  n follows round(H/28) * round(W/28) --
+# patch 14 and a 2x2 merge -- for five of the six rows; the 640 x 960 row prints 529 where the
+# rule gives 782, and the rule is used here.  The paper does not describe the encoder behind the
+# table beyond its output width: the workload runs the long-sequence encoder (C4: 27 layers,
+# hidden 1152 = 16 x 72, MLP 4304, LayerNorm, 2-D rotary, output width 3584) at patch 14 with a
+# temporal patch of 2: a still image enters as a clip of two frames and one temporal slice (t = 1),
+# the way encoders that share one patch embedding between images and video take it -- and a patch
+# row of 3 * 2 * 14 * 14 = 1176 elements is a multiple of 8, which the bf16 kernels require and
+# 3 * 14 * 14 = 588 is not.
+T42_SIZES_PX = ((280, 280), (560, 560), (640, 960), (720, 1280), (1080, 1920), (4096, 3112))
+T42 = C4.replace(name="T42-table4_2-bf16-patch14", patch=14, temporal_patch=2)
+
+
+def t42_grid(h_px: int, w_px: int) -> Tuple[int, int, int]:
+    """Patch grid of one Table 4_2 image: 2 * round(side / 28) patches of 14 pixels per side."""
+    return (1, 2 * int(round(h_px / 28.0)), 2 * int(round(w_px / 28.0)))
+
+
 # Canonical C3 image sizes in pixels (H, W): 32 draws of multiples of 32 in [224, 1344]
 # from default_rng(1).integers(7, 43, (32, 2)) * 32, frozen here so that a change in
 # NumPy's bit stream cannot change the workload.
@@ -99,10 +118,12 @@ def grids_for(cfg: EncoderConfig) -> List[Tuple[int, int, int]]:
         return [(1, 168, 168)]
     if cfg.name == C5.name:
         return [(8, 32, 32)] * 4
+    if cfg.name == T42.name:
+        return [t42_grid(h, w) for h, w in T42_SIZES_PX]
     raise KeyError(cfg.name)
 
 
-CONFIGS: Dict[str, EncoderConfig] = {"C1": C1, "C2": C2, "C3": C3, "C4": C4, "C5": C5}
+CONFIGS: Dict[str, EncoderConfig] = {"C1": C1, "C2": C2, "C3": C3, "C4": C4, "C5": C5, "T42": T42}
 
 
 # ------------------------------------------------------------------ dtype rounding

@@ -279,6 +279,114 @@ def test_c5_full_video_batch_one_layer_last_clip_against_oracle():
     check(cfg, got[3 * nm:], ref, "clip 4 of 4, 8192 tokens")
 
 
+def test_c5_full_video_batch_one_layer_per_frame_segments_last_clip_against_oracle():
+    """The video batch with one attention segment per frame (windowed attention: 32 segments of
+    1024 tokens instead of 4 of 8192; rotary coordinates still run over the whole clip), one layer;
+    the oracle recomputes the last clip with the same per-frame segments."""
+    from paper_2601_11590_amd import binding as B
+    import torch
+    cfg = W.C5.replace(num_layers=1)
+    grids = W.grids_for(W.C5)
+    log("case %s: 4 clips, per-frame segments, L=1; oracle on the last clip" % cfg.name)
+    gw, layers = W.all_weights(cfg)
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids, "frame")
+    assert len(cu) - 1 == 32 and int(cu[1]) == 1024
+    enc = B.EpdEncoder(cfg, gw, layers, max_tokens=patches.shape[0], max_segments=len(cu) - 1, max_items=len(grids))
+    try:
+        got = enc.encode(B.to_device_patches(patches, cfg.dtype), cu, grid)
+        torch.cuda.synchronize()
+        got = got.float().cpu().numpy()
+    finally:
+        enc.close()
+    n, nm = W.num_tokens(grids[:1]), W.num_merged_tokens(grids[:1], cfg.merge)
+    cu1, g1 = W.metadata(grids[3:], "frame")
+    ref = O.encode(cfg, gw, layers, patches[3 * n:], cu1, g1)
+    check(cfg, got[3 * nm:], ref, "clip 4 of 4, 8 frame segments of 1024 tokens")
+
+
+def oracle_rows_one_layer(cfg, gw, lw, patches, cu, grid, merged_rows):
+    """Rows `merged_rows` of the one-layer encoder's output, computed one window at a time from
+    the oracle's own functions: keys and values of the whole batch (three matrix products), then
+    for every sampled visual token the softmax rows of its merge x merge source tokens only."""
+    H, d, D = cfg.num_heads, cfg.head_dim, cfg.hidden
+    x = O.linear(patches, gw["patch_w"], gw.get("patch_b"))
+    a = O.norm(cfg, x, lw["norm1_g"], lw.get("norm1_b"))
+    theta = O.rotary_angles(O.token_coords(grid), cfg.rope_pairs, cfg.rope_base) if cfg.rope != "none" else None
+    wq, wk, wv = lw["qkv_w"][:D], lw["qkv_w"][D:2 * D], lw["qkv_w"][2 * D:]
+    bq, bk, bv = (lw["qkv_b"][i * D:(i + 1) * D] for i in range(3)) if "qkv_b" in lw else (None, None, None)
+    T = x.shape[0]
+    k = O.linear(a, wk, bk).reshape(T, H, d)
+    v = O.linear(a, wv, bv).reshape(T, H, d)
+    if theta is not None:
+        k = O.apply_rotary(k, theta)
+    idx = O.merge_gather_index(grid, cfg.merge)[merged_rows]                 # [rows, merge^2] source tokens
+    tok = np.unique(idx.ravel())
+    q = O.linear(a[tok], wq, bq).reshape(len(tok), H, d)
+    if theta is not None:
+        q = O.apply_rotary(q, theta[tok])
+    seg = np.searchsorted(np.asarray(cu), tok, side="right") - 1
+    o = np.zeros((len(tok), H, d))
+    for i, t in enumerate(tok):
+        s0, s1 = int(cu[seg[i]]), int(cu[seg[i] + 1])
+        for h in range(H):
+            p = O.softmax_rows((q[i:i + 1, h] @ k[s0:s1, h].T) / np.sqrt(float(d)))
+            o[i, h] = p @ v[s0:s1, h]
+    xs = x[tok] + O.linear(o.reshape(len(tok), D), lw["proj_w"], lw.get("proj_b"))
+    b = O.norm(cfg, xs, lw["norm2_g"], lw.get("norm2_b"))
+    xs = xs + O.linear(O.activation(cfg, O.linear(b, lw["fc1_w"], lw.get("fc1_b"))), lw["fc2_w"], lw.get("fc2_b"))
+    z = O.norm(cfg, xs, gw["final_norm_g"], gw.get("final_norm_b"))
+    pos = {int(t): i for i, t in enumerate(tok)}
+    g = np.stack([np.concatenate([z[pos[int(t)]] for t in row]) for row in idx])
+    return O.linear(g, gw["merge_w"], gw.get("merge_b"))
+
+
+def test_oracle_rows_one_layer_helper_equals_the_oracle():
+    # the sampled-row evaluation used below for sequences too long for the full oracle, checked
+    # against the full oracle on a batch it can do (CPU arithmetic only)
+    cfg = small("bf16", num_layers=1, norm="layernorm", num_heads=2, head_dim=72, hidden=144, rope_pairs=(0, 18, 18))
+    gw, layers = W.all_weights(cfg)
+    patches = W.packed_patches(cfg, GRIDS)
+    cu, grid = W.metadata(GRIDS)
+    ref = O.encode(cfg, gw, layers, patches, cu, grid)
+    rows = np.array([0, 3, 14, 15, 16, 40, ref.shape[0] - 1])
+    assert np.abs(oracle_rows_one_layer(cfg, gw, layers[0], patches, cu, grid, rows) - ref[rows]).max() < 1e-10
+
+
+def test_table_4_2_batch_token_counts_and_parity():
+    """The six resolutions of the paper's Table 4_2 (section 4.2) as one packed batch at patch 14
+    (85 500 patch tokens, segments of 400 ... 64 824 tokens), one layer.  The library's output has
+    one row per visual token: per image that is the count the table prints (100, 400, 1196, 2691,
+    16 206; 782 by the rule for the inconsistent 640 x 960 row).  The five smaller images are
+    compared with the oracle in full, the 64 824-token image on sampled rows."""
+    from paper_2601_11590_amd import binding as B
+    import torch
+    cfg = W.T42.replace(num_layers=1)
+    grids = W.grids_for(W.T42)
+    log("case %s: %s, L=1" % (cfg.name, grids))
+    gw, layers = W.all_weights(cfg)
+    patches = W.packed_patches(cfg, grids)
+    cu, grid = W.metadata(grids)
+    enc = B.EpdEncoder(cfg, gw, layers, max_tokens=patches.shape[0], max_segments=len(grids), max_items=len(grids))
+    try:
+        got = enc.encode(B.to_device_patches(patches, cfg.dtype), cu, grid)
+        torch.cuda.synchronize()
+        got = got.float().cpu().numpy()
+    finally:
+        enc.close()
+    counts = [W.num_merged_tokens([g], cfg.merge) for g in grids]
+    assert counts == [100, 400, 782, 1196, 2691, 16206]
+    assert got.shape == (sum(counts), 3584) and np.isfinite(got).all()
+    n5 = W.num_tokens(grids[:5])
+    cu5, g5 = W.metadata(grids[:5])
+    ref5 = O.encode(cfg, gw, layers, patches[:n5], cu5, g5)
+    check(cfg, got[:sum(counts[:5])], ref5, "images 1-5 (280^2 ... 1080 x 1920)")
+    first = sum(counts[:5])
+    rows = first + np.unique(np.round(np.linspace(0, counts[5] - 1, 24)).astype(np.int64))
+    ref6 = oracle_rows_one_layer(cfg, gw, layers[0], patches, cu, grid, rows)
+    check(cfg, got[rows], ref6, "image 6 (4096 x 3112, 64824 tokens), %d sampled rows" % len(rows))
+
+
 def test_c3_full_depth_varlen_batch_smallest_images_against_oracle():
     """The largest batch of the benchmark configurations at its full depth (32 images of mixed
     sizes, 73 896 tokens, 24 layers) in one call; the oracle recomputes the three smallest

@@ -30,7 +30,7 @@ def test_patchify_element_order():
 
 def test_config_table_shapes():
     want = {"C1": (256, 1, 64), "C2": (6272, 8, 1568), "C3": (73896, 32, 18474),
-            "C4": (28224, 1, 7056), "C5": (32768, 4, 8192)}
+            "C4": (28224, 1, 7056), "C5": (32768, 4, 8192), "T42": (85500, 6, 21375)}
     for key, cfg in W.CONFIGS.items():
         grids = W.grids_for(cfg)
         assert cfg.hidden == cfg.num_heads * cfg.head_dim
@@ -39,6 +39,25 @@ def test_config_table_shapes():
         assert (W.num_tokens(grids), len(grids), W.num_merged_tokens(grids)) == want[key]
         assert cu[0] == 0 and cu[-1] == want[key][0] and g.shape == (len(grids), 3)
     assert W.C1.patch_dim == 588 and W.C2.patch_dim == 768 and W.C5.patch_dim == 1176
+
+
+def test_table_4_2_workload_reproduces_the_visual_token_counts_the_paper_prints():
+    """The T42 batch is the six resolutions of the paper's Table 4_2 at patch 14 with a 2x2 merge;
+    its per-image visual-token counts must be the table's (five consistent rows; the 640 x 960 row
+    is inconsistent in the paper itself and follows the rule here)."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_table4_2_token_counts.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert [(int(r[0]), int(r[1])) for r in rows] == list(W.T42_SIZES_PX)
+    grids = W.grids_for(W.T42)
+    for r, g in zip(rows, grids):
+        n = W.num_merged_tokens([g], W.T42.merge)
+        if int(r[4]):
+            assert n == int(r[2]), (r, g)
+        else:
+            assert n != int(r[2]) and n == 782
+        assert int(r[3]) == W.T42.out_dim == 3584
+    assert W.T42.patch == 14 and W.T42.patch_dim == 1176 and W.T42.head_dim == 72
 
 
 def test_c3_canonical_sizes_follow_the_stated_draw():
