@@ -343,6 +343,109 @@ def preprocess_and_store(res, with_store):
     return prep, store_res
 
 
+def colocation(splits):
+    """Operator-level co-location (paper section 3.5, "Physical Co-Location and Spatial
+    Multiplexing": stages with dissimilar resource demands disturb each other least).  The
+    encoder (C2 batch: matrix cores + exp) runs on a stream restricted by a CU mask to `a` of the
+    256 compute units while a neighbour runs on a stream restricted to the other 256 - a: either a
+    synthetic memory-bound kernel (epd_probe_stream_read over 2 GiB: a decode-like streaming read)
+    or a second encoder.  Every entry is time beside the neighbour / time alone ON THE SAME MASK, so
+    what is measured is interference through what the two still share (HBM, the caches behind the
+    CUs, power), not the loss of compute units.  Prints one JSON line."""
+    import ctypes as C
+    import torch
+    from paper_2601_11590_amd import binding as B, workloads as W
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipExtStreamCreateWithCUMask.argtypes = [C.POINTER(C.c_void_p), C.c_uint32, C.POINTER(C.c_uint32)]
+    hip.hipExtStreamCreateWithCUMask.restype = C.c_int
+    ncu = torch.cuda.get_device_properties(0).multi_processor_count
+    words = (ncu + 31) // 32
+
+    def masked_stream(lo, hi):
+        """Stream whose kernels may only use logical compute units [lo, hi).  The driver deals the
+        logical units of the mask out to the eight XCDs in turn, so a contiguous range takes the same
+        share of every XCD."""
+        bits = (C.c_uint32 * words)()
+        for cu in range(lo, hi):
+            bits[cu // 32] |= 1 << (cu % 32)
+        h = C.c_void_p()
+        rc = hip.hipExtStreamCreateWithCUMask(C.byref(h), words, bits)
+        assert rc == 0 and h.value, "hipExtStreamCreateWithCUMask failed (%d)" % rc
+        return torch.cuda.ExternalStream(h.value)
+
+    cfg = W.C2
+    grids = W.grids_for(cfg)
+    T, Tm = W.num_tokens(grids), W.num_merged_tokens(grids, cfg.merge)
+    gw = W.global_weights(cfg)
+    layers = [W.layer_weights(cfg, l) for l in range(cfg.num_layers)]
+    patches = B.to_device_patches(W.packed_patches(cfg, grids), cfg.dtype)
+    cu, grid = W.metadata(grids)
+    encs = [B.EpdEncoder(cfg, gw, layers, max_tokens=T, max_segments=len(grids), max_items=len(grids)) for _ in range(2)]
+    outs = [torch.empty((Tm, cfg.out_dim), dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]
+    nbytes = 2 << 30
+    bufs = [torch.ones(nbytes // 4, dtype=torch.int32, device="cuda:0") for _ in range(2)]
+    sums = [torch.zeros(65536, dtype=torch.float32, device="cuda:0") for _ in range(2)]
+
+    def op_encode(slot, stream, n_cu):
+        encs[slot].encode(patches, cu, grid, outs[slot])
+
+    def op_read(slot, stream, n_cu):
+        B.epd_probe_stream_read(bufs[slot].data_ptr(), nbytes, sums[slot].data_ptr(), 16 * n_cu, stream.cuda_stream)
+
+    ops = {"encode": (op_encode, 6), "read": (op_read, 12)}
+
+    def timed(a, sa, na, b=None, sb=None, nb=0, b_reps=0):
+        """ms per launch of op `a` on stream sa, optionally while op `b` keeps stream sb busy."""
+        fa, reps = ops[a]
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if b is not None:
+            with torch.cuda.stream(sb):
+                for _ in range(b_reps):
+                    ops[b][0](1, sb, nb)
+        with torch.cuda.stream(sa):
+            fa(0, sa, na)
+            e0.record()
+            for _ in range(reps):
+                fa(0, sa, na)
+            e1.record()
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        torch.cuda.synchronize()
+        return ms
+
+    full = masked_stream(0, ncu)
+    ref = {k: timed(k, full, ncu) for k in ops}
+    log("[colocation] all %d CUs: encode %.3f ms per C2 call, read %.3f ms per 2 GiB (%.0f GB/s)" % (ncu, ref["encode"], ref["read"], nbytes / ref["read"] / 1e6))
+    rows = []
+    for a_cus in splits:
+        sa, sb = masked_stream(0, a_cus), masked_stream(a_cus, ncu)
+        nb = ncu - a_cus
+        alone = {("encode", "A"): timed("encode", sa, a_cus), ("read", "A"): timed("read", sa, a_cus),
+                 ("encode", "B"): timed("encode", sb, nb), ("read", "B"): timed("read", sb, nb)}
+        row = {"cus_measured": a_cus, "cus_neighbour": nb,
+               "encode_alone_ms": alone["encode", "A"], "read_alone_GBs_on_neighbour_cus": nbytes / alone["read", "B"] / 1e6}
+        for a in ops:
+            for b in ops:
+                # the neighbour's queue lasts several times longer than the measured run
+                need = 4.0 * alone[a, "A"] * (ops[a][1] + 1)
+                b_reps = int(need / alone[b, "B"]) + 2
+                row["%s_beside_%s" % (a, b)] = timed(a, sa, a_cus, b, sb, nb, b_reps) / alone[a, "A"]
+        # and the other way round for the mixed pair: the reader on the small mask beside the encoder
+        need = 4.0 * alone["read", "B"] * (ops["read"][1] + 1)
+        row["read_on_neighbour_cus_beside_encode"] = timed("read", sb, nb, "encode", sa, a_cus, int(need / alone["encode", "A"]) + 2) / alone["read", "B"]
+        rows.append(row)
+        log("[colocation] encoder on %3d CUs (%.3f ms alone), neighbour on %3d: encode beside read x%.2f, beside encode x%.2f | "
+            "read beside read x%.2f, beside encode x%.2f | read on the %d CUs (%.0f GB/s alone) beside the encoder x%.2f"
+            % (a_cus, alone["encode", "A"], nb, row["encode_beside_read"], row["encode_beside_encode"], row["read_beside_read"],
+               row["read_beside_encode"], nb, nbytes / alone["read", "B"] / 1e6, row["read_on_neighbour_cus_beside_encode"]))
+    print(json.dumps({"experiment": "operator co-location on CU-masked streams: time beside the neighbour / time alone on the same mask, one MI355X",
+                      "all_cus": {"encode_ms": ref["encode"], "read_ms": ref["read"], "read_GBs": nbytes / ref["read"] / 1e6},
+                      "splits": rows}), flush=True)
+    for e in encs:
+        e.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -360,6 +463,9 @@ def main():
                     help="only run a plain 1 GiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--in-flight", type=int, default=1,
                     help="batches in flight on separate streams (serving mode; default 1 = one stream)")
+    ap.add_argument("--colocation", default=None, metavar="CUS[,CUS...]",
+                    help="only run the co-location experiment (section 3.5): compute units given to the encoder's stream, "
+                         "e.g. 224,192,128; the neighbour's stream gets the others")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -368,6 +474,9 @@ def main():
         sys.exit(2)
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.colocation:
+        colocation([int(v) for v in args.colocation.split(",")])
+        return
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
         dst = torch.empty_like(src)

@@ -292,6 +292,15 @@ epd_status epd_encode_set_timing(epd_handle h, int32_t step);
 epd_status epd_encode_get_timing(epd_handle h, double* total_ms, int64_t* launches,
                                  double* work);
 
+/* Synthetic memory-bound neighbour for the co-location experiment (section 3.5: stages with
+ * dissimilar resource demands share one device): one launch streams device_buf[0, bytes) once
+ * (16-byte loads, bytes rounded down to a multiple of 16, buffer 16-byte aligned) with `blocks`
+ * blocks of 256 threads (1 .. 65536) and writes one value per block to device_out[blocks].
+ * Asynchronous on `stream`; allocates nothing.  EPD_ERR_INVALID_ARG on a NULL or misaligned
+ * pointer, bytes < 16 or a block count out of range. */
+epd_status epd_probe_stream_read(const void* device_buf, uint64_t bytes, float* device_out,
+                                 int32_t blocks, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

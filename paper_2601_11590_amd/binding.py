@@ -59,7 +59,7 @@ EXPORTS = ["epd_encode_workspace_bytes", "epd_encode_create", "epd_encode", "epd
            "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing", "epd_encode_set_tuning",
            "epd_encode_get_timing", "epd_preprocess", "epd_encode_cached", "epd_store_create",
            "epd_store_destroy", "epd_store_last_error", "epd_store_hash", "epd_store_hash_noalloc", "epd_store_lookup", "epd_store_insert",
-           "epd_store_stats"]
+           "epd_store_stats", "epd_probe_stream_read"]
 
 
 def _load() -> C.CDLL:
@@ -102,6 +102,8 @@ def _load() -> C.CDLL:
     lib.epd_encode_debug_hidden.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.epd_encode_set_timing.restype = C.c_int
     lib.epd_encode_set_timing.argtypes = [C.c_void_p, C.c_int32]
+    lib.epd_probe_stream_read.restype = C.c_int
+    lib.epd_probe_stream_read.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.epd_encode_set_tuning.restype = C.c_int
     lib.epd_encode_set_tuning.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.epd_encode_get_timing.restype = C.c_int
@@ -278,6 +280,12 @@ def epd_encode_set_tuning(handle, gemm_tile: int, attn_groups: int) -> None:
     st = lib.epd_encode_set_tuning(handle, gemm_tile, attn_groups)
     if st != EPD_OK:
         raise EpdError(st, epd_encode_last_error(handle))
+
+
+def epd_probe_stream_read(buf_ptr: int, nbytes: int, out_ptr: int, blocks: int, stream: int) -> None:
+    st = lib.epd_probe_stream_read(buf_ptr, nbytes, out_ptr, blocks, stream)
+    if st != EPD_OK:
+        raise EpdError(st, "epd_probe_stream_read: bad argument or launch failure")
 
 
 def epd_encode_get_timing(handle):

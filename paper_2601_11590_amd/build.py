@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libepd_encode.so")
 STAMP = LIB + ".hash"         # source_hash() of the sources LIB was built from
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["epd_api.hip", "plan_norm.hip", "preprocess.hip", "mm_store.hip", "kernels_f32.hip", "gemm_bf16.hip", "attn_bf16.hip"]
+SOURCES = ["epd_api.hip", "plan_norm.hip", "preprocess.hip", "mm_store.hip", "probe.hip", "kernels_f32.hip", "gemm_bf16.hip", "attn_bf16.hip"]
 
 # packed fp32 instructions are switched off for every kernel (hipcc -O3 would otherwise form
 # them from ordinary float code)

@@ -19,7 +19,7 @@ HEADER = os.path.join(ROOT, "include", "epd_encode.h")
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(epd_(?:encode|preprocess|store)\w*)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(epd_(?:encode|preprocess|store|probe)\w*)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
