@@ -10,11 +10,15 @@
 //     maximum and the running sum of the softmax are per-lane scalars; one exchange between
 //     the two lane halves (v_permlane32_swap) per key tile completes the maximum, the sums
 //     are merged once at the end.
-//   * The accumulator layout of S^T (key rows 8*(v/4) + 4*(lane/32) + v%4) is, after rounding
-//     to bf16, directly the second MFMA operand of O^T = V^T P^T, provided the first operand
-//     (V^T) enumerates the keys in the same order.  V is therefore kept transposed
-//     ([channel][token], written that way by the QKV GEMM) and a lane reads its 2 x 4 keys
-//     with two 8-byte LDS reads.  No data ever moves between lanes for P.
+//   * The accumulator layout of S^T (rows 8*(v/4) + 4*(lane/32) + v%4) is, after rounding to
+//     bf16, directly the second MFMA operand of O^T = V^T P^T, provided the first operand
+//     (V^T) enumerates the keys in the same order.  A lane's accumulator rows come in runs of
+//     four, eight apart; the K tile is therefore laid out in LDS with rows 4-7 and 8-11 of
+//     every 16 exchanged (row r holds key r with bits 2 and 3 swapped -- free, since every
+//     lane of a direct-to-LDS load picks its own source row), which makes the eight values a
+//     lane feeds into one MFMA eight CONSECUTIVE keys.  V is kept transposed ([channel][token],
+//     written that way by the QKV GEMM) in natural key order, and a lane reads its 8 keys with
+//     one 16-byte LDS read.  No data ever moves between lanes for P.
 //   * K tiles ([64 keys][d]) and V^T tiles ([d][64 keys]) go from global memory straight into
 //     LDS (global_load_lds_dwordx4) in a two-stage ring: the tile after the current one is in
 //     flight while the current one is multiplied, one barrier per key tile.  Rows of 128 bytes
@@ -35,7 +39,6 @@ namespace epd {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 #define EPD_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define EPD_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -46,7 +49,6 @@ constexpr float kLag = 8.0f;   // slack of the running softmax reference, in log
 union Frag8 {
   bf16x8 v;
   uint4 u;
-  u32x2 h[2];
   uint32_t w[4];
 };
 
@@ -59,9 +61,6 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 template <int OFF> __device__ __forceinline__ void lds_read16(bf16x8& d, uint32_t addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
 }
-template <int OFF> __device__ __forceinline__ void lds_read8(u32x2& d, uint32_t addr) {
-  asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(OFF) : "memory");
-}
 // The compiler takes the result of an inline ds_read for valid at once; the ties that follow a
 // wait keep the consumers behind it, and the scheduling barrier keeps any register copy the
 // compiler makes for a tie behind it as well (a copy hoisted above the wait would read a
@@ -72,6 +71,9 @@ template <int PENDING> __device__ __forceinline__ void lds_wait() {
   __builtin_amdgcn_sched_barrier(0);
 }
 __device__ __forceinline__ void tie(bf16x8& f) { asm volatile("" : "+v"(f)); }
+
+// Key (within its tile) held by row r of the K tile in LDS: bits 2 and 3 of r exchanged.
+__device__ __forceinline__ constexpr int key_of_row(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 // max over the two halves of the wave (lane l and lane l ^ 32)
 __device__ __forceinline__ float half_swap_max(float x) {
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     const int lin = it * 256 + tid;
     k_on[it] = lin < BKV * CPRK;
     const int row = lin / CPRK, slot = lin - row * CPRK;
-    k_row[it] = row;
+    k_row[it] = key_of_row(row);   // LDS row `row` receives this key of the tile
     k_ch[it] = SWZK ? (slot ^ ((CPRK == 8 ? (row >> 1) : row) & (CPRK - 1))) : slot;
   }
   uint32_t v_off[LV];
@@ -185,9 +187,11 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     const int slot = SWZK ? (ch ^ ((CPRK == 8 ? (l32 >> 1) : l32) & (CPRK - 1))) : ch;
     k_rd[ks] = lds0 + l32 * ROWK + slot * 16;
   }
-  uint32_t v_rd[8];   // chunk kb*4 + mm*2 + half of row l32 (row blocks of 32 keep the swizzle)
+  // V^T fragment f = kb*2 + mm: keys 16 f + 8 lg .. + 7 of channel row l32 = 16-byte chunk
+  // 2 f + lg of that row (row blocks of 32 keep the swizzle)
+  uint32_t v_rd[4];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) v_rd[c] = lds0 + KBYTES + l32 * 128 + ((c ^ ((l32 >> 1) & 7)) * 16) + lg * 8;
+  for (int f = 0; f < 4; ++f) v_rd[f] = lds0 + KBYTES + l32 * 128 + (((2 * f + lg) ^ ((l32 >> 1) & 7)) * 16);
 
   // a wave none of whose query rows exist still takes part in loads and barriers only
   const int q_wave0 = w.q0 + wave * 32 * NQ;
@@ -272,7 +276,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int kvl = kb * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
+          const int kvl = kb * 32 + key_of_row(8 * (v >> 2) + (v & 3)) + 8 * lg;   // key of accumulator row 8 (v/4) + 4 lg + v%4
           if (kvl >= nvalid) {
 #pragma unroll
             for (int nq = 0; nq < NQ; ++nq) s[kb][nq][v] = -INFINITY;
@@ -354,10 +358,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     auto read_v = [&](auto DBI, int buf) {
       constexpr int off = SO + decltype(DBI)::value * 32 * 128;
 #pragma unroll
-      for (int f = 0; f < 4; ++f) {   // f = kb*2 + mm
-        lds_read8<off>(vf[buf][f].h[0], v_rd[2 * f]);
-        lds_read8<off>(vf[buf][f].h[1], v_rd[2 * f + 1]);
-      }
+      for (int f = 0; f < 4; ++f) lds_read16<off>(vf[buf][f].v, v_rd[f]);   // f = kb*2 + mm
     };
     auto pv = [&](int db, int buf) {
 #pragma unroll
@@ -371,7 +372,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     auto pv_blocks = [&](auto self, auto DBI) {
       constexpr int db = decltype(DBI)::value;
       if constexpr (db < DBX) {
-        if constexpr (db + 1 < DBX) { read_v(std::integral_constant<int, db + 1>{}, (db + 1) & 1); lds_wait<8>(); } else { lds_wait<0>(); }
+        if constexpr (db + 1 < DBX) { read_v(std::integral_constant<int, db + 1>{}, (db + 1) & 1); lds_wait<4>(); } else { lds_wait<0>(); }
         pv(db, db & 1);
         self(self, std::integral_constant<int, db + 1>{});
       }

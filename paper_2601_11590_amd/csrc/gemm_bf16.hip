@@ -757,6 +757,12 @@ static void launch_cfg(const GemmArgs& g, hipStream_t s) {
     // keep the A panels of one group (group_m x BM rows x K) within about 2 MB of the 4 MB L2
     const long panel = (long)T::BM * g.K * 2;
     a.group_m = (int)std::max(1L, std::min((long)tiles_m, (2L << 20) / std::max(panel, 1L)));
+    // Long K (panels beyond the cache) and a wide output: the 32 tiles an XCD runs at a time still
+    // advance through K together, so what has to stay cached is their current K window, not whole
+    // panels.  Four row tiles per group make that set 4 x 8 tiles (12 operand panels) instead of
+    // 1 x 32 (33 panels): +5 % on 32768 x 12800 x 3200 and 32768 x 9600 x 3200; narrow outputs
+    // (13 column tiles) measured best with the panel rule alone.
+    if (tiles_n >= 24) a.group_m = std::max(a.group_m, 4);
     // Few rows against a large weight matrix (the merger projection): with row groups every
     // XCD streams all of W.  When the whole grid runs in at most two rounds, number the tiles
     // column by column instead, so that an XCD owns a block of columns: W is then fetched
