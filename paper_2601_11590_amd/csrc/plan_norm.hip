@@ -91,9 +91,17 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-template <typename T> __device__ __forceinline__ float ld_param(const T* p, int i);
-template <> __device__ __forceinline__ float ld_param<float>(const float* p, int i) { return p[i]; }
-template <> __device__ __forceinline__ float ld_param<__bf16>(const __bf16* p, int i) { return (float)p[i]; }
+
+template <typename T> __device__ __forceinline__ void ld_param4(const T* p, int i, float* o);
+template <> __device__ __forceinline__ void ld_param4<float>(const float* p, int i, float* o) {
+  const float4 v = *(const float4*)(p + i);
+  o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+}
+template <> __device__ __forceinline__ void ld_param4<__bf16>(const __bf16* p, int i, float* o) {
+  const uint2 v = *(const uint2*)(p + i);
+  o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+  o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+}
 
 // One 64-lane wave per token row; the row is held in registers (NV float4 per lane) between
 // the statistics pass and the scaling pass, so HBM sees one read and one write per element.
@@ -132,13 +140,12 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
     int c = (i * 64 + lane) * 4;
     if (c < D) {
       float y[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+      // the four gains (and shifts) of the chunk come in one load each (c is a multiple of 4)
+      float g4[4], b4[4] = {0.f, 0.f, 0.f, 0.f};
+      ld_param4(gamma, c, g4);
+      if (beta) ld_param4(beta, c, b4);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float g = ld_param(gamma, c + e);
-        float r = (y[e] - mean) * rstd * g;
-        if (beta) r += ld_param(beta, c + e);
-        y[e] = r;
-      }
+      for (int e = 0; e < 4; ++e) y[e] = (y[e] - mean) * rstd * g4[e] + b4[e];
       if constexpr (sizeof(OT) == 4) {
         *(float4*)((float*)orow + c) = make_float4(y[0], y[1], y[2], y[3]);
       } else {
