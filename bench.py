@@ -141,8 +141,11 @@ def stored_traffic(name, step):
     return val, "profiles/%s" % os.path.basename(path)
 
 
-def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="item", keep_inputs=False):
-    """Times `steps` epd_encode calls of configuration `name`.  Returns a dict of results."""
+def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="item", keep_inputs=False, zero_data=False):
+    """Times `steps` epd_encode calls of configuration `name`.  Returns a dict of results.
+    zero_data: every weight and every input element is zero -- the same kernels and launches on
+    operands that toggle no wires, which shows how much of the time on real data is the chip's
+    power limit rather than the kernels' own pipelines (never the headline)."""
     import torch
     from paper_2601_11590_amd import binding as B, workloads as W
     cfg = W.CONFIGS[name]
@@ -157,10 +160,14 @@ def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="it
     patches = W.packed_patches(cfg, grids)
     layer0 = W.layer_weights(cfg, 0) if cfg.num_layers > 0 else None
     kept_layers = []
+    if zero_data:
+        gw = {k: np.zeros_like(v) for k, v in gw.items()}
+        patches = np.zeros_like(patches)
+        layer0 = {k: np.zeros_like(v) for k, v in layer0.items()} if layer0 else None
 
     def layer_stream():     # one layer at a time: 45 layers of C5 would be 22 GB of float32 on the host
         for l in range(cfg.num_layers):
-            lw = layer0 if l == 0 else W.layer_weights(cfg, l)
+            lw = layer0 if (l == 0 or zero_data) else W.layer_weights(cfg, l)
             if keep_inputs:
                 kept_layers.append(lw)
             yield lw
@@ -242,7 +249,7 @@ def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="it
     achieved = dom_work / (dom_ms * 1e-3) / 1e12
     log("[bench] %s: %.3f ms/step, %.0f visual tokens/s, %.1f TFLOP/s end to end (%.1f%% of bf16 peak); dominant kernel %s at %.1f TFLOP/s"
         % (cfg.name, ms_per_step, Tm * steps / dt, tfl, 100 * tfl / PEAK_BF16_TFLOPS, dom, achieved))
-    traffic, traffic_src = (None, "depth or segments differ from the profiled run") if (layers_override is not None or segments != "item" or in_flight != 1) \
+    traffic, traffic_src = (None, "depth, segments or data differ from the profiled run") if (layers_override is not None or segments != "item" or in_flight != 1 or zero_data) \
         else stored_traffic(name, dom)
     res = {
         "name": name, "cfg": cfg, "grids": grids, "cu": cu, "grid": grid, "T": T, "Tm": Tm,
@@ -446,6 +453,31 @@ def colocation(splits):
         e.close()
 
 
+def mfma_peak():
+    """Practical ceiling of the bf16 matrix pipes (epd_probe_mfma_rate: register-resident operands,
+    no memory traffic) for both instruction shapes, on random and on all-zero operands.  Prints one
+    JSON line."""
+    import torch
+    from paper_2601_11590_amd import binding as B
+    out = torch.zeros(256 * 512, dtype=torch.float32, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    res = {}
+    for shape, sname in ((0, "v_mfma_f32_32x32x16_bf16"), (1, "v_mfma_f32_16x16x32_bf16")):
+        for zero in (False, True):
+            B.epd_probe_mfma_rate(shape, zero, 200, out.data_ptr(), st)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fl = B.epd_probe_mfma_rate(shape, zero, 20000, out.data_ptr(), st)
+            e1.record()
+            torch.cuda.synchronize()
+            tf = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            res["%s, %s operands" % (sname, "all-zero" if zero else "random")] = tf
+            log("[mfma-peak] %-28s %-8s operands: %7.1f TFLOP/s (%.1f%% of %.0f)" % (sname, "all-zero" if zero else "random", tf, 100 * tf / PEAK_BF16_TFLOPS, PEAK_BF16_TFLOPS))
+    print(json.dumps({"experiment": "bf16 matrix-core rate on register-resident operands, 2 waves per SIMD on all 256 CUs, TFLOP/s",
+                      "published_peak": PEAK_BF16_TFLOPS, "measured": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -463,6 +495,11 @@ def main():
                     help="only run a plain 1 GiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--in-flight", type=int, default=1,
                     help="batches in flight on separate streams (serving mode; default 1 = one stream)")
+    ap.add_argument("--zero-data", action="store_true",
+                    help="experiment: all weights and inputs zero (same kernels, no operand toggling): the pipeline-bound rate "
+                         "beside the power-bound rate of the default run; never the headline")
+    ap.add_argument("--mfma-peak", action="store_true",
+                    help="only measure the matrix-core rate on register-resident operands (random and all-zero)")
     ap.add_argument("--colocation", default=None, metavar="CUS[,CUS...]",
                     help="only run the co-location experiment (section 3.5): compute units given to the encoder's stream, "
                          "e.g. 224,192,128; the neighbour's stream gets the others")
@@ -477,6 +514,9 @@ def main():
     if args.colocation:
         colocation([int(v) for v in args.colocation.split(",")])
         return
+    if args.mfma_peak:
+        mfma_peak()
+        return
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
         dst = torch.empty_like(src)
@@ -486,14 +526,15 @@ def main():
         log("[bench] copied 5 x 1 GiB (reads 1 GiB and writes 1 GiB per launch)")
         return
 
-    plain = args.layers is None and args.segments == "item" and args.in_flight == 1
+    plain = args.layers is None and args.segments == "item" and args.in_flight == 1 and not args.zero_data
     small = args.config in ("C2", "C3")           # the oracle runs these at full depth in seconds
-    head = measure(args.config, args.steps, args.warmup, args.in_flight, args.layers, args.segments, keep_inputs=small and not args.no_cpu)
+    head = measure(args.config, args.steps, args.warmup, args.in_flight, args.layers, args.segments,
+                   keep_inputs=small and not args.no_cpu and not args.zero_data, zero_data=args.zero_data)
     prep, store_res = preprocess_and_store(head, with_store=args.config == "C2" and plain)
     gpu_out = head["out"].float().cpu().numpy()
     stored = stored_rows_parity(args.config, gpu_out) if plain else None
     cpu = None
-    if not args.no_cpu:
+    if not args.no_cpu and not args.zero_data:
         if small:
             n = len(head["grids"]) if args.config == "C2" else 3
             cpu = cpu_baseline_full(head["cfg"], head["gw"], head["layers"], head["patches"], head["grid"], gpu_out, n) if args.segments == "item" else None

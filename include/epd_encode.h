@@ -301,6 +301,19 @@ epd_status epd_encode_get_timing(epd_handle h, double* total_ms, int64_t* launch
 epd_status epd_probe_stream_read(const void* device_buf, uint64_t bytes, float* device_out,
                                  int32_t blocks, void* stream);
 
+/* Matrix-core rate on register-resident operands (no memory traffic): the practical ceiling of
+ * the bf16 matrix pipes under the chip's power limit, which depends on the operand values.
+ *   shape          0 = v_mfma_f32_32x32x16_bf16 (the instruction the encoder's kernels use),
+ *                  1 = v_mfma_f32_16x16x32_bf16
+ *   zero_operands  0 = random operands of magnitude [0.5, 1), 1 = all-zero operands
+ *   iters          loop trips per wave (> 0)
+ *   device_out     device float [256 * 512]: one value per thread (keeps the work observable)
+ *   flops_per_launch  HOST out (may be NULL): flops one launch executes
+ * Launches 256 blocks of 512 threads on `stream`; allocates nothing.  EPD_ERR_INVALID_ARG on a bad
+ * shape, iters <= 0 or a NULL output. */
+epd_status epd_probe_mfma_rate(int32_t shape, int32_t zero_operands, int32_t iters,
+                               float* device_out, double* flops_per_launch, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

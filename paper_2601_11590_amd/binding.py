@@ -59,7 +59,7 @@ EXPORTS = ["epd_encode_workspace_bytes", "epd_encode_create", "epd_encode", "epd
            "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing", "epd_encode_set_tuning",
            "epd_encode_get_timing", "epd_preprocess", "epd_encode_cached", "epd_store_create",
            "epd_store_destroy", "epd_store_last_error", "epd_store_hash", "epd_store_hash_noalloc", "epd_store_lookup", "epd_store_insert",
-           "epd_store_stats", "epd_probe_stream_read"]
+           "epd_store_stats", "epd_probe_stream_read", "epd_probe_mfma_rate"]
 
 
 def _load() -> C.CDLL:
@@ -104,6 +104,8 @@ def _load() -> C.CDLL:
     lib.epd_encode_set_timing.argtypes = [C.c_void_p, C.c_int32]
     lib.epd_probe_stream_read.restype = C.c_int
     lib.epd_probe_stream_read.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.epd_probe_mfma_rate.restype = C.c_int
+    lib.epd_probe_mfma_rate.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
     lib.epd_encode_set_tuning.restype = C.c_int
     lib.epd_encode_set_tuning.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.epd_encode_get_timing.restype = C.c_int
@@ -286,6 +288,15 @@ def epd_probe_stream_read(buf_ptr: int, nbytes: int, out_ptr: int, blocks: int, 
     st = lib.epd_probe_stream_read(buf_ptr, nbytes, out_ptr, blocks, stream)
     if st != EPD_OK:
         raise EpdError(st, "epd_probe_stream_read: bad argument or launch failure")
+
+
+def epd_probe_mfma_rate(shape: int, zero_operands: bool, iters: int, out_ptr: int, stream: int) -> float:
+    """Enqueue one launch of the matrix-core rate probe; returns the flops it executes."""
+    fl = C.c_double()
+    st = lib.epd_probe_mfma_rate(shape, 1 if zero_operands else 0, iters, out_ptr, C.byref(fl), stream)
+    if st != EPD_OK:
+        raise EpdError(st, "epd_probe_mfma_rate: bad argument or launch failure")
+    return fl.value
 
 
 def epd_encode_get_timing(handle):

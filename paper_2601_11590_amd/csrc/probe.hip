@@ -34,7 +34,62 @@ __global__ __launch_bounds__(kThreads) void stream_read_kernel(const uint4* __re
   if (threadIdx.x == 0) out[blockIdx.x] = (float)(part[0] & 0xffffff);
 }
 
+// ---- matrix-core rate on register-resident operands: no memory traffic at all, so what it
+// measures is the matrix pipes under the chip's power limit.  Every wave cycles through eight
+// A and eight B fragments (both operands change with every instruction) and four accumulators.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__device__ inline bf16x8 probe_fragment(uint32_t& s, bool zero) {
+  union { bf16x8 v; uint32_t w[4]; } u;
+  for (int i = 0; i < 4; ++i) {
+    s = s * 1664525u + 1013904223u;
+    // two bf16 values of magnitude [0.5, 1) with random sign and mantissa
+    u.w[i] = zero ? 0u : (((s & 0x807f) | 0x3f00) | ((((s >> 16) & 0x807f) | 0x3f00) << 16));
+  }
+  return u.v;
+}
+
+template <int SHAPE>   // 0: v_mfma_f32_32x32x16_bf16, 1: v_mfma_f32_16x16x32_bf16
+__global__ __launch_bounds__(512) void mfma_rate_kernel(int iters, int zero, float* out) {
+  uint32_t seed = threadIdx.x * 9781u + blockIdx.x * 7919u + 1u;
+  bf16x8 a[8], b[8];
+  for (int i = 0; i < 8; ++i) { a[i] = probe_fragment(seed, zero != 0); b[i] = probe_fragment(seed, zero != 0); }
+  float s = 0.f;
+  if constexpr (SHAPE == 0) {
+    f32x16 acc[4];
+    for (int i = 0; i < 4; ++i) for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 7], b[(i * 3 + 1) & 7], acc[i & 3], 0, 0, 0);
+    }
+    for (int i = 0; i < 4; ++i) for (int v = 0; v < 16; ++v) s += acc[i][v];
+  } else {
+    f32x4 acc[4];
+    for (int i = 0; i < 4; ++i) for (int v = 0; v < 4; ++v) acc[i][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 64; ++i) acc[i & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i & 7], b[(i * 3 + 1) & 7], acc[i & 3], 0, 0, 0);
+    }
+    for (int i = 0; i < 4; ++i) for (int v = 0; v < 4; ++v) s += acc[i][v];
+  }
+  out[blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 }  // namespace
+
+// 256 blocks of 8 waves (two per SIMD on a 256-CU chip).  One launch executes
+// 256 * 8 * iters * 32 * 32768 flops: a 32x32x16 instruction is 2 * 32 * 32 * 16 = 32768 flops and a
+// wave issues 32 of them per iteration (or 64 of the half-sized 16x16x32).
+extern "C" epd_status epd_probe_mfma_rate(int32_t shape, int32_t zero_operands, int32_t iters, float* device_out,
+                                          double* flops_per_launch, void* stream) {
+  if ((shape != 0 && shape != 1) || iters <= 0 || !device_out) return EPD_ERR_INVALID_ARG;
+  if (shape == 0) hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(256), dim3(512), 0, (hipStream_t)stream, iters, zero_operands, device_out);
+  else hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(256), dim3(512), 0, (hipStream_t)stream, iters, zero_operands, device_out);
+  if (flops_per_launch) *flops_per_launch = 256.0 * 8.0 * (double)iters * 32.0 * 32768.0;
+  return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
+}
 
 extern "C" epd_status epd_probe_stream_read(const void* device_buf, uint64_t bytes, float* device_out, int32_t blocks,
                                             void* stream) {
