@@ -797,22 +797,28 @@ using T5 = Tile<320, 256, 64, 2, 4, 1>;   // 8 waves, 160x64 wave tiles, 144 KB 
 // Each is priced by the output area its busiest compute unit works through -- rounds of
 // blocks x blocks per unit x tile area -- over a measured relative rate, and the 256 x 256
 // tile is kept unless another is clearly (5 %) cheaper.
+// Cost of an M x N output as one launch of one tile shape: the output area the busiest compute
+// unit works through -- rounds of blocks x blocks per unit x tile area -- over a measured relative
+// rate.  Returns the cheapest shape (the 256 x 256 tile unless another is 5 % cheaper).
+static double tile_cost(int M, int N, int bm, int bn, int blocks, double rate) {
+  const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+  const long slots = (long)num_cus() * blocks;
+  return (double)((tiles + slots - 1) / slots) * blocks * bm * bn / rate;
+}
+static int cheapest_tile(int M, int N, double* cost_out) {
+  const double c0 = tile_cost(M, N, 256, 256, 1, 1.0), c4 = tile_cost(M, N, 128, 128, 2, 0.85), c5 = tile_cost(M, N, 320, 256, 1, 0.9);
+  int t = 0;
+  double best = c0 * 0.95, real = c0;
+  if (c4 < best) { t = 4; best = real = c4; }
+  if (c5 < best) { t = 5; best = real = c5; }
+  if (cost_out) *cost_out = real;
+  return t;
+}
+
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
   int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1;   // tile_cfg: set by the tuning hook of the C ABI
-  if (t != 0 && t != 2 && t != 4 && t != 5) {
-    const long cus = num_cus();
-    auto cost = [&](int bm, int bn, int blocks, double rate) {
-      const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
-      const long slots = cus * blocks;
-      return (double)((tiles + slots - 1) / slots) * blocks * bm * bn / rate;
-    };
-    const double c0 = cost(256, 256, 1, 1.0), c4 = cost(128, 128, 2, 0.85), c5 = cost(320, 256, 1, 0.9);
-    t = 0;
-    double best = c0 * 0.95;
-    if (c4 < best) { t = 4; best = c4; }
-    if (c5 < best) { t = 5; best = c5; }
-  }
+  if (t != 0 && t != 2 && t != 4 && t != 5) t = cheapest_tile(g.M, g.N, nullptr);
   if (EPI == EPI_QKV && (t == 0 || t == 5) && g.qk_cols % 256 != 0) t = 2;
   switch (t) {
     case 0: launch_cfg<T0, EPI, OUT, GATHER>(g, s); break;
@@ -824,8 +830,47 @@ static void launch_epi(const GemmArgs& g, hipStream_t s) {
 
 constexpr int kQkvBN = 128;
 
+// Rows to hand to whole rounds of 256 x 256 tiles when the rest is better served by 128 x 128
+// tiles (0 = launch the output as one piece).  A grid of 6.5 rounds of 256 x 256 tiles costs 7: the
+// compute units that get no tile in the last round idle for a whole tile time.  Cutting the output
+// behind the last full round and covering the remaining rows with 128 x 128 tiles (two blocks per
+// unit, a quarter of the area each) turns that last round into about 0.6 of one: 32768 x 3200
+// (13 column tiles, 1664 tiles) becomes 30208 rows in 6 rounds plus 2560 rows as 500 small tiles.
+static int body_rows_before_small_tile_tail(const GemmArgs& g) {
+  if (g.tile_cfg != 0 || g.gather || g.epilogue == EPI_QKV) return 0;
+  const long cus = num_cus();
+  const long tm = (g.M + 255) / 256, tn = (g.N + 255) / 256;
+  const long full = tm * tn / cus;                       // complete rounds of the big tile
+  if (full < 1 || (tm * tn) % cus == 0) return 0;
+  const long body_tm = full * cus / tn;                  // row tiles that fit into them
+  if (body_tm <= 0 || body_tm >= tm) return 0;
+  double whole = 0.0;
+  if (cheapest_tile(g.M, g.N, &whole) != 0) return 0;    // another single shape already wins
+  const int tail_rows = g.M - (int)body_tm * 256;
+  const double split = (double)full * 256 * 256 + tile_cost(tail_rows, g.N, 128, 128, 2, 0.85);
+  return split < 0.98 * whole ? (int)body_tm * 256 : 0;
+}
+
+static void launch_gemm_bf16_whole(const GemmArgs& g, hipStream_t s);
+
 void launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
+  const int mb = body_rows_before_small_tile_tail(g);
+  if (mb <= 0) { launch_gemm_bf16_whole(g, s); return; }
+  GemmArgs body = g, tail = g;
+  body.M = mb; body.tile_cfg = 1;                        // 256 x 256
+  tail.M = g.M - mb; tail.tile_cfg = 5;                  // 128 x 128
+  tail.A = (const __bf16*)g.A + (size_t)mb * g.lda;
+  if (g.out) tail.out = g.out_f32 ? (void*)((float*)g.out + (size_t)mb * g.ldo) : (void*)((__bf16*)g.out + (size_t)mb * g.ldo);
+  if (g.resid) tail.resid = g.resid + (size_t)mb * g.ldr;
+  if (g.xb) tail.xb = (__bf16*)g.xb + (size_t)mb * g.ldxb;
+  if (g.stats_out) tail.stats_out = g.stats_out + (size_t)mb * g.stats_n;
+  if (g.stats_in) tail.stats_in = g.stats_in + (size_t)mb * g.stats_n;
+  launch_gemm_bf16_whole(body, s);
+  launch_gemm_bf16_whole(tail, s);
+}
+
+static void launch_gemm_bf16_whole(const GemmArgs& g, hipStream_t s) {
   switch (g.epilogue) {
     case EPI_STORE:
       if (g.gather) launch_epi<EPI_STORE, OUT_BF16, true>(g, s);
