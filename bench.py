@@ -208,6 +208,12 @@ def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="it
         es = 2 if cfg.dtype == "bf16" else 4
         gbytes = (Tm * cfg.merge ** 2 * cfg.hidden + cfg.out_dim * cfg.merge ** 2 * cfg.hidden + Tm * cfg.out_dim) * es
         steps_roof["merge"]["gather_algorithmic_GBs"] = gbytes / (table["merge"][0] * 1e-3) / 1e9
+    if "qkv" in steps_roof and cfg.rope != "none":
+        # rotary is fused into the QKV epilogue: what it adds to that kernel's memory side is the
+        # (cos, sin) table of the call, T x d/2 pairs of 8 bytes, read once per launch algorithmically
+        rbytes = T * (cfg.head_dim // 2) * 8
+        steps_roof["qkv"]["fused_rotary_table_bytes_per_launch"] = rbytes
+        steps_roof["qkv"]["fused_rotary_algorithmic_GBs"] = rbytes / (steps_roof["qkv"]["avg_launch_ms"] * 1e-3) / 1e9
     mat_steps = [k for k in steps_roof if k != "norm"]
     dom = max(mat_steps, key=lambda k: table[k][0])
     dom_id = B.STEP_NAMES.index(dom)
