@@ -1,27 +1,28 @@
 // bf16 GEMM family of the Encode-stage library (ViT forward, paper section 3.1, Eq. 1):
 // patch embedding, QKV projection with rotary epilogue, attention output projection, the
 // two MLP GEMMs and the merger projection all are  C[M,N] = A[M,K] * W[N,K]^T (+bias)  with
-// different epilogues.  Written for gfx950: 64-lane waves, v_mfma_f32_32x32x16_bf16 (fp32
-// accumulate), operand tiles brought from global memory straight into LDS
-// (global_load_lds_dwordx4, no register staging) in a multi-stage ring.
+// different epilogues.  Written for gfx950: 64-lane waves, v_mfma_f32_16x16x32_bf16 (fp32
+// accumulate; at equal flops this shape draws less power than the 32x32x16 one, and under the
+// chip's power limit that is clock: +7 % on the large GEMMs with random operands, nothing on
+// all-zero ones), operand tiles brought from global memory straight into LDS
+// (global_load_lds_dwordx4, no register staging) in a two-stage ring.
 //
 // Tile scheme.  A block of WAVES_M x WAVES_N waves owns a BM x BN output tile; K advances in
 // steps of BK.  Both operands are K-contiguous in memory ("NT" form), so one lane's MFMA
 // operand (8 consecutive k of one row) is one 16-byte LDS read.  A direct-to-LDS load writes
 // the 64 lanes' 16-byte chunks to consecutive LDS addresses, so rows cannot be padded;
 // instead the chunk a lane fetches is chosen so that chunk c of row r lands in slot
-// c ^ swz(r) of that row, which spreads the 32 rows read by one MFMA operand fetch over all
-// bank groups.  Stage s+STAGES-1 is in flight while stage s is multiplied; one barrier per
-// K step.
+// c ^ swz(r) of that row, which spreads the 16 rows read by one MFMA operand fetch over all
+// bank groups.  Stage s+1 is in flight while stage s is multiplied; one barrier per K step.
 //
-// Accumulator orientation.  For a 32x32 MFMA result lane l holds column (l % 32) and rows
-// 8*(v/4) + 4*(l/32) + (v%4), v = 0..15.  By default the W fragment is fed as the first
-// operand, so "rows" are output columns n and the lane's column is a token m: every lane then
-// owns runs of 4 consecutive n of one token -- 16-byte fp32 / 8-byte bf16 row-major stores,
-// and the two members of a rotary pair (neighbouring n after the create-time reorder) share
-// a lane.  For the V third of the QKV projection the operands are swapped, a lane owns 4
-// consecutive tokens of one n, and V is stored transposed ([channel][token]) for the
-// attention kernel's second GEMM.
+// Accumulator orientation.  For a 16x16 MFMA result lane l holds column (l % 16) and rows
+// 4*(l/16) + v, v = 0..3.  By default the W fragment is fed as the first operand, so "rows"
+// are output columns n and the lane's column is a token m: every lane then owns runs of 4
+// consecutive n of one token -- 16-byte fp32 / 8-byte bf16 pieces of a row, and the two
+// members of a rotary pair (neighbouring n after the create-time reorder) share a lane.  For
+// the V third of the QKV projection the operands are swapped, a lane owns 4 consecutive tokens
+// of one n, and V is stored transposed ([channel][token]) for the attention kernel's second
+// GEMM.
 #include "epd_internal.h"
 
 #include <algorithm>
@@ -31,7 +32,7 @@ namespace epd {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 #define EPD_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define EPD_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -111,20 +112,32 @@ template <int N, int STRIDE, int BASE, int I = 0> __device__ __forceinline__ voi
 // makes for a tie behind it as well -- a copy hoisted above the wait reads a register the LDS
 // has not filled yet (seen once, with a variant of the main loop; the generated code of every
 // kernel is checked for such copies at build time, check_lds_waits.py).
-template <int PENDING, int N> __device__ __forceinline__ void wait_lds_reads(bf16x8* f) {
+template <int PENDING, int N, int N2> __device__ __forceinline__ void wait_lds_reads(bf16x8* f, bf16x8* f2) {
   asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(PENDING) : "memory");
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
+#pragma unroll
+  for (int i = 0; i < N2; ++i) asm volatile("" : "+v"(f2[i]));
+}
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), unrolled at compile time
+template <class F, int... I> __device__ __forceinline__ void static_for_seq(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f) {
+  static_for_seq(f, std::make_integer_sequence<int, N>{});
 }
 
 // Compile-time description of one kernel variant.
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int MINBLK_>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int MINBLK_, int PARTS_>
 struct Tile {
   static constexpr int BM = BM_, BN = BN_, BK = BK_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int MINBLK = MINBLK_;
   static constexpr int NT = 64 * WAVES_M * WAVES_N;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
+  static constexpr int TM16 = WM / 16, TN16 = WN / 16;   // 16 x 16 MFMA blocks per wave tile
+  static constexpr int PARTS = PARTS_;                   // parts the A blocks of a k step are multiplied in
   static constexpr int CPR = BK / 8;                     // 16-byte chunks per tile row
   static constexpr int LA = BM * CPR / NT, LW = BN * CPR / NT;   // load instructions per thread and stage
   static constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
@@ -134,12 +147,12 @@ struct Tile {
   static constexpr int EPI_BYTES_A = BM * (BN / EPI_PASSES * 4 + 16), EPI_BYTES_V = (BN / EPI_PASSES) * (BM * 4 + 16);
   static constexpr int LDS_BYTES = (2 * STAGE_BYTES > EPI_BYTES_A ? 2 * STAGE_BYTES : EPI_BYTES_A) > EPI_BYTES_V
                                        ? (2 * STAGE_BYTES > EPI_BYTES_A ? 2 * STAGE_BYTES : EPI_BYTES_A) : EPI_BYTES_V;
-  static_assert(BK == 32 || BK == 64, "BK");
+  static_assert(BK == 64, "BK: the main loop is written for two MFMA k steps of 32 per stage");
   static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0, "tile / thread mismatch");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
   // LDS has 64 banks of 4 bytes: a 16-byte-per-lane read is served 16 lanes (256 bytes) at a
   // time, so 16 consecutive rows must map to 16 different 16-byte columns modulo 256 bytes.
-  __device__ static __forceinline__ int swz(int row) { return BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+  __device__ static __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 };
 
 template <class T, int EPI, int OUT, bool VMODE, bool GATHER, bool FAST>
@@ -153,7 +166,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS bases scalar
   const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
-  const int l32 = lane & 31, lg = lane >> 5;
+  const int l16 = lane & 15, g4 = lane >> 4;
 
   const char* zeros = (const char*)g.zeros;
   const int kcw = GATHER ? g.K / g.gather_n : g.K;
@@ -267,14 +280,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   // largest tile has no registers to spare for them and fetches them in the epilogue
   constexpr bool BF16_EPI = (EPI == EPI_STORE || EPI == EPI_GELU) && OUT == OUT_BF16 && !VMODE;
   constexpr bool BIAS_PRE = BF16_EPI && BM * BN <= 256 * 256;
-  [[maybe_unused]] uint2 bb[TN][4];
+  [[maybe_unused]] uint2 bb[TN][2];
   auto load_bias = [&]() {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nb = n0 + wn * WN + j * 32 + q * 8 + lg * 4;
-        bb[j][q] = (g.bias && nb < g.N) ? *(const uint2*)((const uint16_t*)g.bias + nb) : make_uint2(0u, 0u);   // N is a multiple of 4
+      for (int c = 0; c < 2; ++c) {
+        const int nb = n0 + wn * WN + j * 32 + c * 16 + g4 * 4;
+        bb[j][c] = (g.bias && nb < g.N) ? *(const uint2*)((const uint16_t*)g.bias + nb) : make_uint2(0u, 0u);   // N is a multiple of 4
       }
   };
   if constexpr (BIAS_PRE) load_bias();
@@ -290,54 +303,74 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     }
   };
 
-  f32x16 acc[TM][TN];
+  // acc[i][j][q]: the 32 x 32 block (i, j) of the wave tile as four 16 x 16 MFMA results,
+  // q = 2 * (token half) + (column half)
+  f32x4 acc[TM][TN][4];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[i][j][q][v] = 0.f;
 
   // ---- LDS fragment reads.  Issued as explicit ds_read_b128 so that their order against the
   // direct-to-LDS loads and the waits below is exactly the one written here (a compiler-
   // visible LDS read that follows a direct-to-LDS load in program order gets a full wait for
   // that load inserted in front of it, which would serialise the two-stage ring).
-  // Row of lane = wave row + i*32 + l32; multiples of 32 keep swz(row) = swz(l32).
-  constexpr int KS = BK / 16, NF = TM + TN;
+  // One fragment = 16 rows x 32 k: lane (l16, g4) reads k chunk 4*ks + g4 of row blk*16 + l16;
+  // multiples of 16 keep swz(row) = swz(l16).  A stage is multiplied in 2 * P slices,
+  // slice sl = (k step ks = sl / P, part p = sl % P of the A blocks): slice (ks, 0) needs the
+  // TN16 W fragments of the k step and the first AP A fragments, the others the next AP A
+  // fragments.  W fragments alternate between two buffers by k step, A fragments by slice.
+  constexpr int TM16 = T::TM16, TN16 = T::TN16, P = T::PARTS, AP = TM16 / P, NSL = 2 * P;
+  static_assert(TM16 % P == 0 && TN16 + AP <= 15, "slices / LDS counter");
   constexpr bool LATE_REFILL = TM * TN <= 4;
   const uint32_t lds0 = (uint32_t)(size_t)EPD_LPTR(lds);
-  // Address of slice ks = address of slice 0 with bits 5.. of the chunk slot flipped (the row
-  // base has zeros there); stage and 32-row block go into the instruction's offset field.
-  const uint32_t a_rd0 = lds0 + (wm * WM + l32) * ROWB + ((lg ^ T::swz(l32)) * 16);
-  const uint32_t w_rd0 = lds0 + 2 * A_BYTES + (wn * WN + l32) * ROWB + ((lg ^ T::swz(l32)) * 16);
-  bf16x8 frag[2][NF];
-  auto read_frags = [&](auto BUF, auto ST, auto KSTEP) {
-    constexpr int buf = decltype(BUF)::value, st = decltype(ST)::value, ks = decltype(KSTEP)::value;
-    ds_read_rows<TM, 32 * ROWB, st * A_BYTES>(&frag[buf][0], a_rd0 ^ (uint32_t)(ks * 32));
-    ds_read_rows<TN, 32 * ROWB, st * W_BYTES>(&frag[buf][TM], w_rd0 ^ (uint32_t)(ks * 32));
+  // Address of k step 1 = address of k step 0 with bit 6 flipped (chunk slot bit 2; the row
+  // base has a zero there); stage and 16-row block go into the instruction's offset field.
+  const uint32_t a_rd0 = lds0 + (wm * WM + l16) * ROWB + ((g4 ^ T::swz(l16)) * 16);
+  const uint32_t w_rd0 = lds0 + 2 * A_BYTES + (wn * WN + l16) * ROWB + ((g4 ^ T::swz(l16)) * 16);
+  bf16x8 fw[2][TN16], fa[2][AP];
+  auto read_slice = [&](auto SL, auto ST) {
+    constexpr int sl = decltype(SL)::value, st = decltype(ST)::value, ks = sl / P, p = sl % P;
+    if constexpr (p == 0) ds_read_rows<TN16, 16 * ROWB, st * W_BYTES>(&fw[ks][0], w_rd0 ^ (uint32_t)(ks * 64));
+    ds_read_rows<AP, 16 * ROWB, st * A_BYTES + p * AP * 16 * ROWB>(&fa[sl & 1][0], a_rd0 ^ (uint32_t)(ks * 64));
   };
-  auto wait_frags = [&](auto BUF, auto PENDING) {
-    wait_lds_reads<decltype(PENDING)::value, NF>(&frag[decltype(BUF)::value][0]);
+  // wait until at most the reads of the next slice are outstanding (none with DRAIN: every
+  // read of the wave has returned), then tie the slice's fragments to the wait
+  auto wait_slice = [&](auto SL, auto DRAIN) {
+    constexpr int sl = decltype(SL)::value, ks = sl / P, p = sl % P;
+    constexpr int next_reads = ((sl + 1) % P == 0 ? TN16 : 0) + AP;
+    wait_lds_reads<(decltype(DRAIN)::value ? 0 : next_reads), AP, (p == 0 ? TN16 : 0)>(&fa[sl & 1][0], &fw[ks][0]);
   };
-  auto mfmas = [&](auto BUF) {
-    constexpr int buf = decltype(BUF)::value;
+  auto mfmas = [&](auto SL) {
+    constexpr int sl = decltype(SL)::value, ks = sl / P, p = sl % P;
     // consecutive MFMAs keep their first operand: measured ~7% faster than alternating it
     if constexpr (VMODE) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int t = 0; t < AP; ++t)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[buf][i], frag[buf][TM + j], acc[i][j], 0, 0, 0);
+        for (int w = 0; w < TN16; ++w) {
+          const int a16 = p * AP + t;
+          acc[a16 >> 1][w >> 1][(a16 & 1) * 2 + (w & 1)] =
+              __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[sl & 1][t], fw[ks][w], acc[a16 >> 1][w >> 1][(a16 & 1) * 2 + (w & 1)], 0, 0, 0);
+        }
     } else {
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int w = 0; w < TN16; ++w)
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[buf][TM + j], frag[buf][i], acc[i][j], 0, 0, 0);
+        for (int t = 0; t < AP; ++t) {
+          const int a16 = p * AP + t;
+          acc[a16 >> 1][w >> 1][(a16 & 1) * 2 + (w & 1)] =
+              __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[ks][w], fa[sl & 1][t], acc[a16 >> 1][w >> 1][(a16 & 1) * 2 + (w & 1)], 0, 0, 0);
+        }
     }
   };
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
+  using LAST = std::integral_constant<int, NSL - 1>;
 
   // Residual rows this thread updates in the epilogue (EPI_RESIDUAL, where its whole share is
   // at most 16 float4): fetched behind the last stage hand-over, so that the read of the
@@ -360,10 +393,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
   };
 
   // ---- main loop: two LDS stages.  The hand-over to the next stage happens before the last
-  // 16-wide k slice of the current stage is multiplied: wait for the own loads of stage s^1,
-  // barrier (everybody's loads landed, everybody finished reading stage s), refill stage s
-  // with K step kt+2, start reading stage s^1 -- and only then issue the MFMAs of the last
-  // slice, which cover the barrier and the LDS latency.  Every load has one full K step to land.
+  // slice of the current stage is multiplied: wait for the own loads of stage s^1, barrier
+  // (everybody's loads landed, everybody finished reading stage s), refill stage s with K step
+  // kt+2, start reading stage s^1 -- and only then issue the MFMAs of the last slice, which
+  // cover the barrier and the LDS latency.  Every load has one full K step to land.
   issue_step(0, 0);
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
@@ -372,43 +405,38 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     row_scale[tid] = 1.0f / sqrtf(fmaf(ss, g.stats_inv_dim, g.stats_eps));
   }
   if (nk > 1) issue_step(1, 1);
-  read_frags(I0{}, I0{}, I0{});
+  read_slice(I0{}, I0{});
 
   auto step = [&](auto S, int kt) {
     constexpr int s = decltype(S)::value;
     using SN = std::integral_constant<int, s ^ 1>;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks < KS - 1) {
-        // fragments of slice ks+1 are requested before slice ks is multiplied
-        if (ks & 1) { if (ks == 1) read_frags(I0{}, S, std::integral_constant<int, (2 < KS ? 2 : 0)>{}); }
-        else { if (ks == 0) read_frags(I1{}, S, I1{}); else read_frags(I1{}, S, std::integral_constant<int, (3 < KS ? 3 : 1)>{}); }
-        if (ks & 1) { wait_frags(I1{}, std::integral_constant<int, NF>{}); mfmas(I1{}); }
-        else { wait_frags(I0{}, std::integral_constant<int, NF>{}); mfmas(I0{}); }
-      } else {
-        // last slice (fragment buffer 1): stage hand-over first
-        if (kt + 1 < nk) {
-          wait_vmcnt<0>();
-          wait_frags(I1{}, I0{});
-          __builtin_amdgcn_s_barrier();
-          if constexpr (!LATE_REFILL) {
-            if (kt + 2 < nk) issue_step(s, kt + 2);
-          }
-          read_frags(I0{}, SN{}, I0{});
-          if (kt + 2 >= nk) prefetch_resid();          // last hand-over: no operand load follows
-        } else {
-          wait_frags(I1{}, I0{});
-        }
-        mfmas(I1{});
-        if constexpr (LATE_REFILL) {
-          // small wave tiles: the refill of stage s is issued behind the queued MFMAs, so the
-          // address arithmetic and load instructions run in their shadow (pinning this order
-          // costs registers, which the large wave tiles do not have)
-          __builtin_amdgcn_sched_barrier(0);
-          if (kt + 2 < nk) issue_step(s, kt + 2);
-          __builtin_amdgcn_sched_barrier(0);
-        }
+    // the fragments of slice sl+1 are requested before slice sl is multiplied
+    static_for<NSL - 1>([&](auto SL) {
+      read_slice(std::integral_constant<int, decltype(SL)::value + 1>{}, S);
+      wait_slice(SL, std::false_type{});
+      mfmas(SL);
+    });
+    // last slice: stage hand-over first
+    if (kt + 1 < nk) {
+      wait_vmcnt<0>();
+      wait_slice(LAST{}, std::true_type{});
+      __builtin_amdgcn_s_barrier();
+      if constexpr (!LATE_REFILL) {
+        if (kt + 2 < nk) issue_step(s, kt + 2);
       }
+      read_slice(I0{}, SN{});
+      if (kt + 2 >= nk) prefetch_resid();          // last hand-over: no operand load follows
+    } else {
+      wait_slice(LAST{}, std::true_type{});
+    }
+    mfmas(LAST{});
+    if constexpr (LATE_REFILL) {
+      // small wave tiles: the refill of stage s is issued behind the queued MFMAs, so the
+      // address arithmetic and load instructions run in their shadow (pinning this order
+      // costs registers, which the large wave tiles do not have)
+      __builtin_amdgcn_sched_barrier(0);
+      if (kt + 2 < nk) issue_step(s, kt + 2);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
   for (int kt = 0; kt < nk; kt += 2) {
@@ -449,7 +477,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
     int tid_v = threadIdx.x;
     asm volatile("" : "+v"(tid_v));
     const int tid = tid_v, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N, l32 = lane & 31, lg = lane >> 5;
+    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N, l16 = lane & 15, g4 = lane >> 4;
     // BM tokens per channel row: BM/8 lanes per row, 8 tokens per lane
     constexpr int LPRV = BM / 8, RPS = NT / LPRV;        // threads beyond RPS whole rows idle
     const int tl = (tid % LPRV) * 8;
@@ -463,19 +491,20 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       __syncthreads();
       if ((wn * WN) / CPV == ps) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int chl = wn * WN + j * 32 + l32;        // channel inside the tile
+        for (int jc = 0; jc < 2 * TN; ++jc) {
+          const int j = jc >> 1, c = jc & 1;
+          const int chl = wn * WN + jc * 16 + l16;       // channel inside the tile
           const float bv = (bias && n0 + chl < g.N) ? bf16_bits_to_float(bias[n0 + chl]) : 0.f;
 #pragma unroll
           for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int ml = wm * WM + i * 32 + q * 8 + lg * 4;
+            for (int t = 0; t < 2; ++t) {
+              const int ml = wm * WM + i * 32 + t * 16 + g4 * 4;
+              const f32x4 a = acc[i][j][2 * t + c];
               float4 rs = make_float4(1.f, 1.f, 1.f, 1.f);
               if (scaled) rs = *(const float4*)(row_scale + ml);
               *(uint2*)(lds + (chl - ps * CPV) * ROWV + ml * 2) =
-                  pack_bf16x4(fmaf(acc[i][j][4 * q], rs.x, bv), fmaf(acc[i][j][4 * q + 1], rs.y, bv),
-                              fmaf(acc[i][j][4 * q + 2], rs.z, bv), fmaf(acc[i][j][4 * q + 3], rs.w, bv));
+                  pack_bf16x4(fmaf(a[0], rs.x, bv), fmaf(a[1], rs.y, bv), fmaf(a[2], rs.z, bv), fmaf(a[3], rs.w, bv));
             }
         }
       }
@@ -516,22 +545,25 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       char* const buf = lds + (i & 1) * BUF;
-      const float rs = scaled ? row_scale[wm * WM + i * 32 + l32] : 1.0f;
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int t = 0; t < 2; ++t) {
+        const float rs = scaled ? row_scale[wm * WM + i * 32 + t * 16 + l16] : 1.0f;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int nl = wn * WN + j * 32 + q * 8 + lg * 4;        // column inside the tile
-          const float b0 = bf16_bits_to_float(bb[j][q].x & 0xffff), b1 = bf16_bits_to_float(bb[j][q].x >> 16);
-          const float b2 = bf16_bits_to_float(bb[j][q].y & 0xffff), b3 = bf16_bits_to_float(bb[j][q].y >> 16);
-          float v0 = fmaf(acc[i][j][4 * q], rs, b0), v1 = fmaf(acc[i][j][4 * q + 1], rs, b1);
-          float v2 = fmaf(acc[i][j][4 * q + 2], rs, b2), v3 = fmaf(acc[i][j][4 * q + 3], rs, b3);
-          if constexpr (EPI == EPI_GELU) {
-            if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
-            else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const int nl = wn * WN + j * 32 + c * 16 + g4 * 4;       // column inside the tile
+            const f32x4 a = acc[i][j][2 * t + c];
+            const float b0 = bf16_bits_to_float(bb[j][c].x & 0xffff), b1 = bf16_bits_to_float(bb[j][c].x >> 16);
+            const float b2 = bf16_bits_to_float(bb[j][c].y & 0xffff), b3 = bf16_bits_to_float(bb[j][c].y >> 16);
+            float v0 = fmaf(a[0], rs, b0), v1 = fmaf(a[1], rs, b1), v2 = fmaf(a[2], rs, b2), v3 = fmaf(a[3], rs, b3);
+            if constexpr (EPI == EPI_GELU) {
+              if (g.act == 0) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
+              else { v0 = gelu_tanh_fast(v0); v1 = gelu_tanh_fast(v1); v2 = gelu_tanh_fast(v2); v3 = gelu_tanh_fast(v3); }
+            }
+            *(uint2*)(buf + (wm * 32 + t * 16 + l16) * ROWO + nl * 2) = pack_bf16x4(v0, v1, v2, v3);
           }
-          *(uint2*)(buf + (wm * 32 + l32) * ROWO + nl * 2) = pack_bf16x4(v0, v1, v2, v3);
-        }
+      }
       __syncthreads();
       if (n < g.N) {
 #pragma unroll
@@ -593,10 +625,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int sr = wm * 32 + l32;
-          const int ch = (wn * WN + j * 32 + q * 8) / 4 + lg;
-          *(float4*)(lds + sr * ROWE + (ch ^ (sr & 15)) * 16) =
-              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+          const int sr = wm * 32 + (q >> 1) * 16 + l16;
+          const int ch = (wn * WN + j * 32 + (q & 1) * 16) / 4 + g4;
+          const f32x4 a = acc[i][j][q];
+          *(float4*)(lds + sr * ROWE + (ch ^ (sr & 15)) * 16) = make_float4(a[0], a[1], a[2], a[3]);
         }
       if (i == 0) wait_vmcnt<0>();
       __syncthreads();
@@ -638,14 +670,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int m0, const
       if (wn / WPH == h) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-          const int ml = wm * WM + i * 32 + l32;
 #pragma unroll
           for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-              const int nl = (wn % WPH) * WN + j * 32 + q * 8 + lg * 4;
-              *(float4*)(lds + ml * ROWE + nl * 4) =
-                  make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+              const int ml = wm * WM + i * 32 + (q >> 1) * 16 + l16;
+              const int nl = (wn % WPH) * WN + j * 32 + (q & 1) * 16 + g4 * 4;
+              const f32x4 a = acc[i][j][q];
+              *(float4*)(lds + ml * ROWE + nl * 4) = make_float4(a[0], a[1], a[2], a[3]);
             }
         }
       }
@@ -783,42 +815,66 @@ static void launch_cfg(const GemmArgs& g, hipStream_t s) {
   hipLaunchKernelGGL((gemm_bf16_kernel<T, EPI, OUT, GATHER, false, 0>), dim3(tiles_m * tiles_n), dim3(T::NT), 0, s, a);
 }
 
-//            BM   BN  BK  WM WN MINBLK
-using T0 = Tile<256, 256, 64, 2, 4, 1>;   // 8 waves, 128x64 wave tiles, 128 KB LDS, one block per CU
-using T2 = Tile<256, 128, 64, 2, 2, 1>;   // 4 waves, 128x64 wave tiles, 96 KB LDS
-using T4 = Tile<128, 128, 64, 2, 2, 2>;   // 4 waves, 64x64 wave tiles, 64 KB LDS, two blocks per CU
-using T5 = Tile<320, 256, 64, 2, 4, 1>;   // 8 waves, 160x64 wave tiles, 144 KB LDS
+//            BM   BN  BK  WM WN MINBLK PARTS
+using T0 = Tile<256, 256, 64, 2, 4, 1, 4>;   // 8 waves, 128x64 wave tiles, 128 KB LDS, one block per CU
+using T2 = Tile<256, 128, 64, 2, 2, 1, 4>;   // 4 waves, 128x64 wave tiles, 96 KB LDS
+using T4 = Tile<128, 128, 64, 2, 2, 2, 4>;   // 4 waves, 64x64 wave tiles, 64 KB LDS, two blocks per CU
+using T5 = Tile<320, 256, 64, 2, 4, 1, 5>;   // 8 waves, 160x64 wave tiles, 144 KB LDS, one block per CU
 
-// Tile choice.  The 256 x 256 tile halves the operand traffic per flop and is the fastest
-// main loop, but runs one block per compute unit; the 128 x 128 tile runs two, which hides
-// the epilogue of one block behind the main loop of the other and quantises better on small
-// grids; the 320 x 256 tile exists for the grids on which it needs one round of blocks less
-// than the others (a 6272 x 3072 output is 240 of its tiles, one round on 256 compute units).
-// Each is priced by the output area its busiest compute unit works through -- rounds of
-// blocks x blocks per unit x tile area -- over a measured relative rate, and the 256 x 256
-// tile is kept unless another is clearly (5 %) cheaper.
-// Cost of an M x N output as one launch of one tile shape: the output area the busiest compute
-// unit works through -- rounds of blocks x blocks per unit x tile area -- over a measured relative
-// rate.  Returns the cheapest shape (the 256 x 256 tile unless another is 5 % cheaper).
-static double tile_cost(int M, int N, int bm, int bn, int blocks, double rate) {
-  const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
-  const long slots = (long)num_cus() * blocks;
-  return (double)((tiles + slots - 1) / slots) * blocks * bm * bn / rate;
+// Tile choice.  Both large tiles run one block per compute unit, so an output whose number of
+// tiles is not a multiple of the unit count pays a whole tile time for its last, partial round.
+// The 128 x 128 tile runs two blocks per unit (the epilogue of one hides behind the main loop of
+// the other) and quantises four times finer, at 0.87 of the rate per unit of output area.  The
+// 320 x 256 tile moves the fewest operand bytes per flop; launched alone in a loop it is 5 - 9 %
+// faster than the 256 x 256 tile, but inside an encoder call -- where the chip sits at its power
+// limit from the first layer to the last -- the two measured equal on every GEMM of the largest
+// configuration, so it is priced at the same rate and wins only where it needs fewer rounds
+// (a 6272 x 3072 output is 240 of its tiles: one round on 256 units instead of two).  A launch is
+// priced by the output area its busiest compute unit works through -- rounds of blocks x blocks
+// per unit x tile area -- over that relative rate.
+struct TileShape { int bm, bn, blocks, cfg; double rate; };
+constexpr TileShape kShape256 = {256, 256, 1, 0, 1.0}, kShape320 = {320, 256, 1, 5, 1.0}, kShape128 = {128, 128, 2, 4, 0.87};
+
+static double tile_cost(int M, int N, const TileShape& t) {
+  const long tiles = (long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+  const long slots = (long)num_cus() * t.blocks;
+  return (double)((tiles + slots - 1) / slots) * t.blocks * t.bm * t.bn / t.rate;
 }
-static int cheapest_tile(int M, int N, double* cost_out) {
-  const double c0 = tile_cost(M, N, 256, 256, 1, 1.0), c4 = tile_cost(M, N, 128, 128, 2, 0.85), c5 = tile_cost(M, N, 320, 256, 1, 0.9);
-  int t = 0;
-  double best = c0 * 0.95, real = c0;
-  if (c4 < best) { t = 4; best = real = c4; }
-  if (c5 < best) { t = 5; best = real = c5; }
-  if (cost_out) *cost_out = real;
-  return t;
+
+// How to cover an M x N output: one launch of `tile`, or (body_rows > 0) the first body_rows rows
+// with `tile` and the rest with 128 x 128 tiles.  The second form cuts the output behind the last
+// full round of the large tile, so that what would have been a partial round of whole-tile
+// times becomes a round of small tiles: 32768 x 3200 in 256 x 256 tiles is 1664 tiles = 6.5
+// rounds, priced 7; cut after 30208 rows it is 6 rounds plus 500 small tiles.
+struct TilePlan { int tile, body_rows; double cost; };
+
+static TilePlan plan_tiles(int M, int N, bool may_split) {
+  TilePlan best = {0, 0, tile_cost(M, N, kShape256)};
+  const double keep = 0.97 * best.cost;          // the plain 256 x 256 launch stays unless clearly beaten
+  auto offer = [&](int tile, int body_rows, double cost) {
+    if (cost < keep && cost < best.cost) best = {tile, body_rows, cost};
+  };
+  offer(kShape128.cfg, 0, tile_cost(M, N, kShape128));
+  offer(kShape320.cfg, 0, tile_cost(M, N, kShape320));
+  if (may_split) {
+    const long cus = num_cus();
+    for (const TileShape* t : {&kShape256, &kShape320}) {
+      const long tm = (M + t->bm - 1) / t->bm, tn = (N + t->bn - 1) / t->bn;
+      const long full = tm * tn / cus;                       // complete rounds of the large tile
+      if (full < 1 || (tm * tn) % cus == 0) continue;
+      const long body_tm = std::min(full * cus / tn, (long)(M / t->bm));   // whole row tiles within them
+      if (body_tm < 1 || body_tm * t->bm >= M) continue;
+      const int body_rows = (int)body_tm * t->bm;
+      offer(t->cfg, body_rows, tile_cost(body_rows, N, *t) + tile_cost(M - body_rows, N, kShape128));
+    }
+  }
+  return best;
 }
 
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
-  int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1;   // tile_cfg: set by the tuning hook of the C ABI
-  if (t != 0 && t != 2 && t != 4 && t != 5) t = cheapest_tile(g.M, g.N, nullptr);
+  int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1;   // tile_cfg: set by the tuning hook of the C ABI, or by a split
+  if (t != 0 && t != 2 && t != 4 && t != 5) t = plan_tiles(g.M, g.N, false).tile;
   if (EPI == EPI_QKV && (t == 0 || t == 5) && g.qk_cols % 256 != 0) t = 2;
   switch (t) {
     case 0: launch_cfg<T0, EPI, OUT, GATHER>(g, s); break;
@@ -830,42 +886,28 @@ static void launch_epi(const GemmArgs& g, hipStream_t s) {
 
 constexpr int kQkvBN = 128;
 
-// Rows to hand to whole rounds of 256 x 256 tiles when the rest is better served by 128 x 128
-// tiles (0 = launch the output as one piece).  A grid of 6.5 rounds of 256 x 256 tiles costs 7: the
-// compute units that get no tile in the last round idle for a whole tile time.  Cutting the output
-// behind the last full round and covering the remaining rows with 128 x 128 tiles (two blocks per
-// unit, a quarter of the area each) turns that last round into about 0.6 of one: 32768 x 3200
-// (13 column tiles, 1664 tiles) becomes 30208 rows in 6 rounds plus 2560 rows as 500 small tiles.
-static int body_rows_before_small_tile_tail(const GemmArgs& g) {
-  if (g.tile_cfg != 0 || g.gather || g.epilogue == EPI_QKV) return 0;
-  const long cus = num_cus();
-  const long tm = (g.M + 255) / 256, tn = (g.N + 255) / 256;
-  const long full = tm * tn / cus;                       // complete rounds of the big tile
-  if (full < 1 || (tm * tn) % cus == 0) return 0;
-  const long body_tm = full * cus / tn;                  // row tiles that fit into them
-  if (body_tm <= 0 || body_tm >= tm) return 0;
-  double whole = 0.0;
-  if (cheapest_tile(g.M, g.N, &whole) != 0) return 0;    // another single shape already wins
-  const int tail_rows = g.M - (int)body_tm * 256;
-  const double split = (double)full * 256 * 256 + tile_cost(tail_rows, g.N, 128, 128, 2, 0.85);
-  return split < 0.98 * whole ? (int)body_tm * 256 : 0;
-}
-
 static void launch_gemm_bf16_whole(const GemmArgs& g, hipStream_t s);
 
 void launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
-  const int mb = body_rows_before_small_tile_tail(g);
-  if (mb <= 0) { launch_gemm_bf16_whole(g, s); return; }
+  // a forced tile, gathered rows, or Q | K columns that do not end on a 256-column boundary
+  // (those run the 256 x 128 tile): one launch
+  const bool may_split = g.tile_cfg == 0 && !g.gather && !(g.epilogue == EPI_QKV && g.qk_cols % 256 != 0);
+  const TilePlan plan = may_split ? plan_tiles(g.M, g.N, true) : TilePlan{0, 0, 0.0};
+  if (plan.body_rows <= 0) { launch_gemm_bf16_whole(g, s); return; }
+  const int mb = plan.body_rows;
   GemmArgs body = g, tail = g;
-  body.M = mb; body.tile_cfg = 1;                        // 256 x 256
-  tail.M = g.M - mb; tail.tile_cfg = 5;                  // 128 x 128
+  body.M = mb; body.tile_cfg = plan.tile + 1;
+  tail.M = g.M - mb; tail.tile_cfg = kShape128.cfg + 1;
+  // everything indexed by the output row moves down by mb rows (vt is indexed through vcol)
   tail.A = (const __bf16*)g.A + (size_t)mb * g.lda;
   if (g.out) tail.out = g.out_f32 ? (void*)((float*)g.out + (size_t)mb * g.ldo) : (void*)((__bf16*)g.out + (size_t)mb * g.ldo);
   if (g.resid) tail.resid = g.resid + (size_t)mb * g.ldr;
   if (g.xb) tail.xb = (__bf16*)g.xb + (size_t)mb * g.ldxb;
   if (g.stats_out) tail.stats_out = g.stats_out + (size_t)mb * g.stats_n;
   if (g.stats_in) tail.stats_in = g.stats_in + (size_t)mb * g.stats_n;
+  if (g.rot) tail.rot = g.rot + (size_t)mb * g.rot_pairs;
+  if (g.vcol) tail.vcol = g.vcol + mb;
   launch_gemm_bf16_whole(body, s);
   launch_gemm_bf16_whole(tail, s);
 }
