@@ -303,8 +303,8 @@ epd_status epd_probe_stream_read(const void* device_buf, uint64_t bytes, float* 
 
 /* Matrix-core rate on register-resident operands (no memory traffic): the practical ceiling of
  * the bf16 matrix pipes under the chip's power limit, which depends on the operand values.
- *   shape          0 = v_mfma_f32_32x32x16_bf16 (the instruction the encoder's kernels use),
- *                  1 = v_mfma_f32_16x16x32_bf16
+ *   shape          0 = v_mfma_f32_32x32x16_bf16 (the attention kernel's instruction),
+ *                  1 = v_mfma_f32_16x16x32_bf16 (the GEMMs')
  *   zero_operands  0 = random operands of magnitude [0.5, 1), 1 = all-zero operands
  *   iters          loop trips per wave (> 0)
  *   device_out     device float [256 * 512]: one value per thread (keeps the work observable)
@@ -313,6 +313,19 @@ epd_status epd_probe_stream_read(const void* device_buf, uint64_t bytes, float* 
  * shape, iters <= 0 or a NULL output. */
 epd_status epd_probe_mfma_rate(int32_t shape, int32_t zero_operands, int32_t iters,
                                float* device_out, double* flops_per_launch, void* stream);
+
+/* Host only, launches nothing: how the bf16 GEMM of the encoder layers would tile an M x N
+ * output (tokens x output columns) on a chip of `compute_units` units (<= 0: the current
+ * device's, 256 where there is none).  The layer GEMMs of V_m = E(I_m) (section 3.1, Eq. 1) run
+ * as one launch of tile_rows x tile_cols tiles, or -- body_rows > 0 -- as that launch over the
+ * first body_rows tokens plus a second launch of 128 x 128 tiles over the rest, which turns a
+ * partial last round of large tiles into a round of small ones.
+ *   qkv_epilogue  1 = the QKV projection (Q | K columns [0, qk_cols), then V), 0 = any other
+ * All three outputs are HOST pointers.  EPD_ERR_INVALID_ARG on M, N <= 0, a NULL output, or
+ * qk_cols outside (0, N] with qkv_epilogue set. */
+epd_status epd_probe_gemm_plan(int32_t M, int32_t N, int32_t qkv_epilogue, int32_t qk_cols,
+                               int32_t compute_units, int32_t* tile_rows, int32_t* tile_cols,
+                               int32_t* body_rows);
 
 #ifdef __cplusplus
 }

@@ -59,7 +59,7 @@ EXPORTS = ["epd_encode_workspace_bytes", "epd_encode_create", "epd_encode", "epd
            "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing", "epd_encode_set_tuning",
            "epd_encode_get_timing", "epd_preprocess", "epd_encode_cached", "epd_store_create",
            "epd_store_destroy", "epd_store_last_error", "epd_store_hash", "epd_store_hash_noalloc", "epd_store_lookup", "epd_store_insert",
-           "epd_store_stats", "epd_probe_stream_read", "epd_probe_mfma_rate"]
+           "epd_store_stats", "epd_probe_stream_read", "epd_probe_mfma_rate", "epd_probe_gemm_plan"]
 
 
 def _load() -> C.CDLL:
@@ -106,6 +106,8 @@ def _load() -> C.CDLL:
     lib.epd_probe_stream_read.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.epd_probe_mfma_rate.restype = C.c_int
     lib.epd_probe_mfma_rate.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
+    lib.epd_probe_gemm_plan.restype = C.c_int
+    lib.epd_probe_gemm_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)] * 3
     lib.epd_encode_set_tuning.restype = C.c_int
     lib.epd_encode_set_tuning.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.epd_encode_get_timing.restype = C.c_int
@@ -503,3 +505,12 @@ class MMStore:
 def to_device_patches(patches_f32: np.ndarray, dtype: str, device: str = "cuda:0") -> torch.Tensor:
     """Host float32 rows (already rounded to ``dtype``) -> device tensor of that dtype."""
     return torch.from_numpy(np.ascontiguousarray(patches_f32)).to(device).to(torch_dtype(dtype)).contiguous()
+
+
+def epd_probe_gemm_plan(M: int, N: int, qkv_epilogue: bool = False, qk_cols: int = 0, compute_units: int = 0):
+    """(tile_rows, tile_cols, body_rows) of the layer GEMM's launch plan for an M x N output (host only)."""
+    tr, tc, br = C.c_int32(), C.c_int32(), C.c_int32()
+    st = lib.epd_probe_gemm_plan(M, N, 1 if qkv_epilogue else 0, qk_cols, compute_units, C.byref(tr), C.byref(tc), C.byref(br))
+    if st != EPD_OK:
+        raise EpdError(st, "epd_probe_gemm_plan: bad argument")
+    return tr.value, tc.value, br.value

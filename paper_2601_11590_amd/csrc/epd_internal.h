@@ -112,6 +112,11 @@ void launch_norm(const float* x, const void* gamma, const void* beta, void* out,
 void launch_gemm_f32(const GemmArgs& g, hipStream_t s);
 bool launch_attn_f32(const AttnArgs& a, hipStream_t s);   // false: head_dim not covered
 void launch_gemm_bf16(const GemmArgs& g, hipStream_t s);
+// How launch_gemm_bf16 would tile g on a chip of compute_units units (<= 0: the current device's;
+// host only, launches nothing): the tile of the first or only launch, and the rows that launch
+// covers when the rest is left to a second launch of 128 x 128 tiles (0 = one launch covers all).
+// Reads M, N, epilogue, qk_cols, gather and tile_cfg of g.
+void plan_gemm_bf16(const GemmArgs& g, int compute_units, int* tile_rows, int* tile_cols, int* body_rows);
 bool launch_attn_bf16(const AttnArgs& a, hipStream_t s);  // false: head_dim not covered
 // query rows per work item for segments up to max_seg_len (0 = unsupported head_dim);
 // never smaller than attn_q_tile(bf16, head_dim, 1).  groups: 0 = the library's choice; 1 or 2 =

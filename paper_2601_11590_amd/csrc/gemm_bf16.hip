@@ -835,9 +835,9 @@ using T5 = Tile<320, 256, 64, 2, 4, 1, 5>;   // 8 waves, 160x64 wave tiles, 144 
 struct TileShape { int bm, bn, blocks, cfg; double rate; };
 constexpr TileShape kShape256 = {256, 256, 1, 0, 1.0}, kShape320 = {320, 256, 1, 5, 1.0}, kShape128 = {128, 128, 2, 4, 0.87};
 
-static double tile_cost(int M, int N, const TileShape& t) {
+static double tile_cost(int M, int N, const TileShape& t, long cus) {
   const long tiles = (long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
-  const long slots = (long)num_cus() * t.blocks;
+  const long slots = cus * t.blocks;
   return (double)((tiles + slots - 1) / slots) * t.blocks * t.bm * t.bn / t.rate;
 }
 
@@ -848,16 +848,15 @@ static double tile_cost(int M, int N, const TileShape& t) {
 // rounds, priced 7; cut after 30208 rows it is 6 rounds plus 500 small tiles.
 struct TilePlan { int tile, body_rows; double cost; };
 
-static TilePlan plan_tiles(int M, int N, bool may_split) {
-  TilePlan best = {0, 0, tile_cost(M, N, kShape256)};
+static TilePlan plan_tiles(int M, int N, bool may_split, long cus) {
+  TilePlan best = {0, 0, tile_cost(M, N, kShape256, cus)};
   const double keep = 0.97 * best.cost;          // the plain 256 x 256 launch stays unless clearly beaten
   auto offer = [&](int tile, int body_rows, double cost) {
     if (cost < keep && cost < best.cost) best = {tile, body_rows, cost};
   };
-  offer(kShape128.cfg, 0, tile_cost(M, N, kShape128));
-  offer(kShape320.cfg, 0, tile_cost(M, N, kShape320));
+  offer(kShape128.cfg, 0, tile_cost(M, N, kShape128, cus));
+  offer(kShape320.cfg, 0, tile_cost(M, N, kShape320, cus));
   if (may_split) {
-    const long cus = num_cus();
     for (const TileShape* t : {&kShape256, &kShape320}) {
       const long tm = (M + t->bm - 1) / t->bm, tn = (N + t->bn - 1) / t->bn;
       const long full = tm * tn / cus;                       // complete rounds of the large tile
@@ -865,7 +864,7 @@ static TilePlan plan_tiles(int M, int N, bool may_split) {
       const long body_tm = std::min(full * cus / tn, (long)(M / t->bm));   // whole row tiles within them
       if (body_tm < 1 || body_tm * t->bm >= M) continue;
       const int body_rows = (int)body_tm * t->bm;
-      offer(t->cfg, body_rows, tile_cost(body_rows, N, *t) + tile_cost(M - body_rows, N, kShape128));
+      offer(t->cfg, body_rows, tile_cost(body_rows, N, *t, cus) + tile_cost(M - body_rows, N, kShape128, cus));
     }
   }
   return best;
@@ -874,7 +873,7 @@ static TilePlan plan_tiles(int M, int N, bool may_split) {
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
   int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1;   // tile_cfg: set by the tuning hook of the C ABI, or by a split
-  if (t != 0 && t != 2 && t != 4 && t != 5) t = plan_tiles(g.M, g.N, false).tile;
+  if (t != 0 && t != 2 && t != 4 && t != 5) t = plan_tiles(g.M, g.N, false, num_cus()).tile;
   if (EPI == EPI_QKV && (t == 0 || t == 5) && g.qk_cols % 256 != 0) t = 2;
   switch (t) {
     case 0: launch_cfg<T0, EPI, OUT, GATHER>(g, s); break;
@@ -888,12 +887,28 @@ constexpr int kQkvBN = 128;
 
 static void launch_gemm_bf16_whole(const GemmArgs& g, hipStream_t s);
 
+// a forced tile, gathered rows, or Q | K columns that do not end on a 256-column boundary (those
+// run the 256 x 128 tile): one launch
+static bool may_split_rows(const GemmArgs& g) {
+  return g.tile_cfg == 0 && !g.gather && !(g.epilogue == EPI_QKV && g.qk_cols % 256 != 0);
+}
+
+void plan_gemm_bf16(const GemmArgs& g, int compute_units, int* tile_rows, int* tile_cols, int* body_rows) {
+  const long cus = compute_units > 0 ? compute_units : num_cus();
+  int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1, body = 0;
+  if (t != 0 && t != 2 && t != 4 && t != 5) {
+    const TilePlan p = plan_tiles(g.M, g.N, may_split_rows(g), cus);
+    t = p.tile; body = p.body_rows;
+  }
+  if (g.epilogue == EPI_QKV && (t == 0 || t == 5) && g.qk_cols % 256 != 0) t = 2;
+  *tile_rows = t == 4 ? 128 : t == 5 ? 320 : 256;
+  *tile_cols = t == 4 || t == 2 ? 128 : 256;
+  *body_rows = body;
+}
+
 void launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
-  // a forced tile, gathered rows, or Q | K columns that do not end on a 256-column boundary
-  // (those run the 256 x 128 tile): one launch
-  const bool may_split = g.tile_cfg == 0 && !g.gather && !(g.epilogue == EPI_QKV && g.qk_cols % 256 != 0);
-  const TilePlan plan = may_split ? plan_tiles(g.M, g.N, true) : TilePlan{0, 0, 0.0};
+  const TilePlan plan = may_split_rows(g) ? plan_tiles(g.M, g.N, true, num_cus()) : TilePlan{0, 0, 0.0};
   if (plan.body_rows <= 0) { launch_gemm_bf16_whole(g, s); return; }
   const int mb = plan.body_rows;
   GemmArgs body = g, tail = g;

@@ -208,3 +208,29 @@ def test_workspace_pads_mlp_width_and_keeps_a_read_tail():
     assert grow_bf16 >= (256 + 128) * 64 * es
     grow_f32 = sizes["f32", 136] - sizes["f32", 128]
     assert 0 < grow_f32 <= (256 + 128 + 128 + 1) * 8 * 4 + 4 * 256
+
+
+def test_gemm_launch_planner_on_the_benchmark_shapes():
+    """Host logic of the bf16 GEMM launcher, read through its probe for a 256-unit chip: one
+    launch of a large tile where its rounds come out whole, the 320 x 256 tile where it saves a
+    round, 128 x 128 tiles on narrow outputs, and a large-tile body plus a small-tile tail where
+    the last round of large tiles would be partial."""
+    from paper_2601_11590_amd import binding as B
+    plan = lambda *a: B.epd_probe_gemm_plan(*a, compute_units=256)
+    # C5 (32 768 tokens, hidden 3200, MLP 12 800): fc1 = 6400 tiles = 25 whole rounds, QKV = 19
+    assert plan(32768, 12800) == (256, 256, 0)
+    assert plan(32768, 9600, True, 6400) == (256, 256, 0)
+    # ... proj / fc2: 1664 tiles = 6.5 rounds -> 6 rounds over 30 208 rows + small tiles
+    assert plan(32768, 3200) == (256, 256, 30208)
+    # C2 (6272 tokens, hidden 1024): QKV is ONE round of 240 320 x 256 tiles; N = 1024 -> 128 x 128
+    assert plan(6272, 3072, True, 2048) == (320, 256, 0)
+    assert plan(6272, 1024) == (128, 128, 0)
+    # Q | K columns that do not end on a 256-column boundary: the 256 x 128 tile, never cut
+    assert plan(13540, 960, True, 640) == (256, 128, 0)
+    # a QKV projection that is cut (13 540 x 1536: 318 tiles -> 1 round + tail)
+    assert plan(13540, 1536, True, 1024) == (256, 256, 10752)
+    # a chip with fewer units changes the rounds, hence the plan
+    assert plan(32768, 3200) != B.epd_probe_gemm_plan(32768, 3200, compute_units=208)
+    for bad in [(0, 128), (128, 0), (128, 128, True, 0), (128, 128, True, 256)]:
+        with pytest.raises(B.EpdError):
+            B.epd_probe_gemm_plan(*bad, compute_units=256)
