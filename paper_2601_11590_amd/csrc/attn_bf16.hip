@@ -29,7 +29,10 @@
 //     the softmax reference value trails the running maximum by up to 8 (log2 units), so the
 //     output accumulators are rescaled only rarely (and then for the whole wave).
 // Head dimensions that are not multiples of 16 / 32 are handled by zeroing the Q operand
-// beyond d and never storing output rows beyond d.
+// beyond d and never storing output rows beyond d; where the channels beyond the last whole
+// 32-row block of O^T fit 16 rows (d = 72) that block is computed with
+// v_mfma_f32_16x16x32_bf16, whose second operand is made from the probability registers by
+// exchanging 16-lane rows (v_permlane16_swap).
 #include "epd_internal.h"
 
 #include <type_traits>
@@ -39,6 +42,7 @@ namespace epd {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 #define EPD_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define EPD_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -92,11 +96,18 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   // SUMROW: row DH of the V^T tile in LDS is a row of ones, so that row DH of O^T accumulates
   // the softmax denominator in the matrix cores (rescaled together with the outputs) instead
   // of 32 vector additions per key tile
-  constexpr int DBX = SUMROW ? (DH + 32) / 32 : DB;   // 32-row blocks of O^T that are computed
+  constexpr int DBX = SUMROW ? (DH + 32) / 32 : DB;   // 32-row blocks of O^T that hold channels or the ones row
+  // TAIL16: the channels beyond the last whole 32-row block, and the ones row, fit 16 rows
+  // (d = 72: channels 64 .. 71 and the ones row).  That block of O^T is then computed with
+  // v_mfma_f32_16x16x32_bf16 -- two 16-query blocks x 32 keys -- at half the matrix-core time
+  // of a 32-row block that would be three quarters padding.
+  constexpr bool TAIL16 = SUMROW && NQ == 1 && (DH % 32) != 0 && (DH % 32) + 1 <= 16;
+  constexpr int DBF = TAIL16 ? DH / 32 : DBX;         // 32-row blocks of O^T computed with the 32x32x16 form
+  constexpr int VROWS = TAIL16 ? DBF * 32 + 16 : DBX * 32;
   constexpr int CPRK = DH / 8;             // 16-byte chunks per K row
   constexpr int ROWK = DH * 2;             // bytes per K row in LDS
   constexpr int KBYTES = BKV * ROWK;
-  constexpr int VBYTES = DBX * 32 * 128;   // V^T tile: DH rows of 64 keys, padded to whole 32-row blocks
+  constexpr int VBYTES = VROWS * 128;      // V^T tile: DH rows of 64 keys, padded to whole blocks of rows
   constexpr int STAGE = KBYTES + VBYTES;
   constexpr int LK = (BKV * CPRK + 255) / 256, LV = (DH * 8 + 255) / 256;
   // K row swizzle: power-of-two rows need one (all rows would start in the same banks);
@@ -123,10 +134,10 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   const char* vbase = (const char*)((const uint16_t*)a.vt + (size_t)head * DH * a.vt_stride + w.vcol0);
   const int ntiles = (w.seg_len + BKV - 1) / BKV;
 
-  // V^T rows DH .. DBX*32-1 of both stages are never loaded: row DH becomes the row of ones
+  // V^T rows DH .. VROWS-1 of both stages are never loaded: row DH becomes the row of ones
   // (SUMROW), the others zero, once, before the first barrier
-  if constexpr (DBX * 32 > DH) {
-    constexpr int PADCH = (DBX * 32 - DH) * 8;   // 16-byte chunks per stage
+  if constexpr (VROWS > DH) {
+    constexpr int PADCH = (VROWS - DH) * 8;      // 16-byte chunks per stage
     for (int i = threadIdx.x; i < 2 * PADCH; i += 256) {
       const int st = i / PADCH, ch = i - st * PADCH;
       const uint32_t fill = (SUMROW && ch < 8) ? 0x3F803F80u : 0u;   // bf16 1.0 pairs
@@ -192,6 +203,14 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   uint32_t v_rd[4];
 #pragma unroll
   for (int f = 0; f < 4; ++f) v_rd[f] = lds0 + KBYTES + l32 * 128 + (((2 * f + lg) ^ ((l32 >> 1) & 7)) * 16);
+  // TAIL16: first operand of the 16x16x32 form = 16 rows x 32 keys, lane (l16, g4) supplies 8 keys
+  // of row l16.  The second operand is made from the two 16-key probability fragments of a
+  // 32-key block by exchanging 16-lane rows (see compute), which puts keys 0-7 | 16-23 | 8-15 |
+  // 24-31 of the block into lane groups g4 = 0 | 1 | 2 | 3: the V^T fragment follows that order,
+  // 16-byte chunk 4 kb + {0, 2, 1, 3}[g4] of row DBF*32 + l16 (kb = 1: address bit 6 flipped).
+  const int l16 = lane & 15, g4 = lane >> 4;
+  [[maybe_unused]] const uint32_t vt_rd = lds0 + KBYTES + (DBF * 32 + l16) * 128 +
+                                          (((((g4 & 1) << 1) | (g4 >> 1)) ^ (((DBF * 32 + l16) >> 1) & 7)) * 16);
 
   // a wave none of whose query rows exist still takes part in loads and barriers only
   const int q_wave0 = w.q0 + wave * 32 * NQ;
@@ -210,13 +229,20 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     }
   }
 
-  f32x16 o[DBX][NQ];
+  f32x16 o[DBF][NQ];
 #pragma unroll
-  for (int db = 0; db < DBX; ++db)
+  for (int db = 0; db < DBF; ++db)
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
       for (int v = 0; v < 16; ++v) o[db][nq][v] = 0.f;
+  // TAIL16: ot[b] = rows DBF*32 .. +15 of O^T for queries 16 b + l16; lane (l16, g4) holds rows
+  // 4 g4 .. 4 g4 + 3 (channels in g4 = 0, 1; the ones row = softmax denominator in g4 = 2, v = 0)
+  [[maybe_unused]] f32x4 ot[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) ot[b][v] = 0.f;
   float mrun[NQ], lrun[NQ];
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) { mrun[nq] = -INFINITY; lrun[nq] = 0.f; }
@@ -343,9 +369,18 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
 #pragma unroll
-        for (int db = 0; db < DBX; ++db)
+        for (int db = 0; db < DBF; ++db)
 #pragma unroll
           for (int v = 0; v < 16; ++v) o[db][nq][v] *= alpha[nq];
+        if constexpr (TAIL16) {
+          // a lane holds the factor of query lane % 32; the 16-query blocks need those of queries
+          // l16 and 16 + l16 in all four lane groups: one exchange of 16-lane rows yields both
+          const auto ab = __builtin_amdgcn_permlane16_swap(__float_as_uint(alpha[nq]), __float_as_uint(alpha[nq]), false, false);
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ot[b][v] *= __uint_as_float(ab[b]);
+        }
         if constexpr (CREF) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) cref[nq][v] = -mrun[nq];
@@ -369,16 +404,44 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
           o[db][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[buf][f].v, pb[nq][f >> 1][f & 1].v, o[db][nq], 0, 0, 0);
       }
     };
+    [[maybe_unused]] bf16x8 vt[2];
     auto pv_blocks = [&](auto self, auto DBI) {
       constexpr int db = decltype(DBI)::value;
-      if constexpr (db < DBX) {
-        if constexpr (db + 1 < DBX) { read_v(std::integral_constant<int, db + 1>{}, (db + 1) & 1); lds_wait<4>(); } else { lds_wait<0>(); }
+      if constexpr (db < DBF) {
+        if constexpr (db + 1 < DBF) {
+          read_v(std::integral_constant<int, db + 1>{}, (db + 1) & 1);
+          lds_wait<4>();
+        } else if constexpr (TAIL16) {
+          lds_read16<SO>(vt[0], vt_rd);
+          lds_read16<SO>(vt[1], vt_rd ^ 64u);
+          lds_wait<2>();
+        } else {
+          lds_wait<0>();
+        }
         pv(db, db & 1);
         self(self, std::integral_constant<int, db + 1>{});
       }
     };
     read_v(std::integral_constant<int, 0>{}, 0);
     pv_blocks(pv_blocks, std::integral_constant<int, 0>{});
+    if constexpr (TAIL16) {
+      lds_wait<0>();
+      tie(vt[0]); tie(vt[1]);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        // x: keys 8 lg .. + 7, y: keys 16 + 8 lg .. + 7 of the block, for query lane % 32.  The
+        // exchange gives x the rows (x0, y0, x2, y2) -- queries 0 .. 15 in every lane group, keys
+        // 0-7 | 16-23 | 8-15 | 24-31 -- and y the rows (x1, y1, x3, y3): queries 16 .. 31.
+        Frag8 x = pb[0][kb][0], y = pb[0][kb][1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const auto r = __builtin_amdgcn_permlane16_swap(x.w[i], y.w[i], false, false);
+          x.w[i] = r[0]; y.w[i] = r[1];
+        }
+        ot[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[kb], x.v, ot[0], 0, 0, 0);
+        ot[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[kb], y.v, ot[1], 0, 0, 0);
+      }
+    }
   };
 
   // ---- key tiles: two-stage ring, the next tile is in flight while this one is multiplied
@@ -402,7 +465,29 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   for (int nq = 0; nq < NQ; ++nq) {
     const int qrow = q_wave0 + nq * 32 + l32;
     float ltot;
-    if constexpr (SUMROW) {
+    if constexpr (TAIL16) {
+      // the denominators of queries l16 / 16 + l16 stand in lanes 32 + l16 of ot[0] / ot[1]
+      // (row 8 of the block = the ones row): bring them to lane groups 0 and 2, then to all four
+      const float t0 = ot[0][0], t1 = ot[1][0];
+      const auto h0 = __builtin_amdgcn_permlane32_swap(__float_as_uint(t0), __float_as_uint(t0), false, false);
+      const auto h1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(t1), __float_as_uint(t1), false, false);
+      const float w0 = __uint_as_float(__builtin_amdgcn_permlane16_swap(h0[1], h0[1], false, false)[0]);
+      const float w1 = __uint_as_float(__builtin_amdgcn_permlane16_swap(h1[1], h1[1], false, false)[0]);
+      ltot = l32 < 16 ? w0 : w1;
+      // channels DBF*32 + 4 g4 .. + 3 of queries 16 b + l16 (lane groups that hold channels)
+      if (4 * g4 < DH - DBF * 32) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int qr = q_wave0 + 16 * b + l16;
+          if (qr >= seg_end) continue;
+          const float inv = 1.0f / (b ? w1 : w0);
+          uint2 pk;
+          pk.x = pack2(ot[b][0] * inv, ot[b][1] * inv);
+          pk.y = pack2(ot[b][2] * inv, ot[b][3] * inv);
+          *(uint2*)(out + (size_t)qr * a.ld_out + head * DH + DBF * 32 + 4 * g4) = pk;
+        }
+      }
+    } else if constexpr (SUMROW) {
       // row DH of O^T: block DH / 32, row r = DH % 32 -> accumulator register 4*(r/8) + r%4 of
       // the lanes of half (r % 8) / 4; the swap hands both halves' values to every lane
       constexpr int r = DH % 32;
@@ -415,7 +500,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
     if (qrow >= seg_end) continue;
     const float inv = 1.0f / ltot;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < (TAIL16 ? DBF : DB); ++db)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int d = db * 32 + q * 8 + lg * 4;
