@@ -133,6 +133,34 @@ def test_bf16_seeded_random_small_configurations(seed):
     parity(cfg, grids, segments=str(rng.choice(["item", "frame"])))
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_bf16_seeded_random_midsize_configurations(seed):
+    # the same kind of draw at sizes that span several tiles of every GEMM shape (hidden 64 .. 1024,
+    # MLP 320 .. 2072, 500 .. 4000 tokens in 2 .. 6 items), with the GEMM tile forced in some draws
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([32, 64, 72, 80, 96, 128]))
+    heads = int(rng.integers(2, 9))
+    rope = str(rng.choice(["none", "2d", "3d"]))
+    half = d // 2
+    if rope == "none":
+        pairs = (0, 0, 0)
+    elif rope == "2d":
+        a = int(rng.integers(1, half)); pairs = (0, a, half - a)
+    else:
+        a = int(rng.integers(1, half - 1)); b = int(rng.integers(1, half - a)); pairs = (a, b, half - a - b)
+    merge = int(rng.choice([1, 2]))
+    patch, tpatch = [(4, 1), (4, 2), (2, 2)][int(rng.integers(0, 3))]
+    cfg = small("bf16", name="mid%d" % seed, num_layers=int(rng.integers(1, 3)), hidden=d * heads, num_heads=heads,
+                head_dim=d, mlp_dim=int(rng.integers(40, 260)) * 8, patch=patch, temporal_patch=tpatch,
+                norm=str(rng.choice(["rmsnorm", "layernorm"])), act=str(rng.choice(["gelu_erf", "gelu_tanh"])),
+                use_bias=bool(rng.integers(0, 2)), rope=rope, rope_pairs=pairs, out_dim=int(rng.integers(20, 120)) * 8,
+                merge=merge, seed=700 + seed)
+    grids = [(int(rng.integers(1, 3)), merge * int(rng.integers(4, 20)), merge * int(rng.integers(4, 20)))
+             for _ in range(int(rng.integers(2, 7)))]
+    tile = int(rng.choice([-1, -1, 0, 2, 4, 5]))
+    parity(cfg, grids, gemm_tile=tile, segments=str(rng.choice(["item", "frame"])))
+
+
 def test_bf16_many_tiles():
     # > 2 row tiles of every GEMM, attention segments with several query and key tiles
     parity(small("bf16", num_layers=3), [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8)])
