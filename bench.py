@@ -33,6 +33,54 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+class PowerSampler:
+    """Board power while a region runs: a thread reads the GPU's hwmon power sensor (microwatts,
+    /sys/class/drm/card*/device/hwmon/hwmon*/power1_input) every 20 ms.  Read-only; where the
+    sensor is not readable the summary is None.  `cap_w` is the board's power limit from the
+    same directory."""
+
+    def __init__(self, period_s=0.02):
+        import glob
+        import threading
+        self.path = next((f for f in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")) if os.access(f, os.R_OK)), None)
+        self.period, self.samples, self._stop = period_s, [], threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True) if self.path else None
+
+    def _read(self, path):
+        try:
+            with open(path) as f:
+                return int(f.read().strip()) / 1e6
+        except (OSError, ValueError):
+            return None
+
+    def _run(self):
+        while not self._stop.is_set():
+            w = self._read(self.path)
+            if w is not None:
+                self.samples.append(w)
+            self._stop.wait(self.period)
+
+    def __enter__(self):
+        if self._thread:
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        if self._thread:
+            self._stop.set()
+            self._thread.join()
+
+    def summary(self, tail=0.75):
+        if not self.samples:
+            return None
+        # the sensor is a moving average over a second or more: the first samples of a region still
+        # hold what ran before it, so the mean is taken over the last `tail` of the samples
+        body = self.samples[int(len(self.samples) * (1.0 - tail)):] or self.samples
+        cap = self._read(os.path.join(os.path.dirname(self.path), "power1_cap"))
+        return {"mean_w": sum(body) / len(body), "max_w": max(self.samples), "samples": len(self.samples), "cap_w": cap,
+                "sensor": "hwmon power1_input, 20 ms period, mean over the last %.0f %% of the region" % (100 * tail)}
+
+
 def host_cores():
     try:
         cores = len(os.sched_getaffinity(0))
@@ -235,13 +283,14 @@ def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="it
     lanes = [(enc, out, torch.cuda.Stream() if extra else torch.cuda.current_stream())] + extra
     enc.set_timing(dom_id)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        e, o, st = lanes[i % len(lanes)]
-        with torch.cuda.stream(st):
-            e.encode(p_dev, cu, grid, o)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    with PowerSampler() as power:
+        t0 = time.perf_counter()
+        for i in range(steps):
+            e, o, st = lanes[i % len(lanes)]
+            with torch.cuda.stream(st):
+                e.encode(p_dev, cu, grid, o)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     dom_ms, dom_n, dom_work = enc.get_timing()
     enc.set_timing(-1)
     if extra:
@@ -255,6 +304,8 @@ def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="it
     achieved = dom_work / (dom_ms * 1e-3) / 1e12
     log("[bench] %s: %.3f ms/step, %.0f visual tokens/s, %.1f TFLOP/s end to end (%.1f%% of bf16 peak); dominant kernel %s at %.1f TFLOP/s"
         % (cfg.name, ms_per_step, Tm * steps / dt, tfl, 100 * tfl / PEAK_BF16_TFLOPS, dom, achieved))
+    if power.summary():
+        log("[bench] board power during the timed steps: mean %.0f W, max %.0f W, limit %.0f W" % (power.summary()["mean_w"], power.summary()["max_w"], power.summary()["cap_w"] or 0))
     traffic, traffic_src = (None, "depth, segments or data differ from the profiled run") if (layers_override is not None or segments != "item" or in_flight != 1 or zero_data) \
         else stored_traffic(name, dom)
     res = {
@@ -265,6 +316,7 @@ def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="it
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
                      "launches": dom_n, "avg_launch_ms": dom_ms / max(dom_n, 1), "flops_per_launch": dom_work / max(dom_n, 1)},
         "rooflines_per_step": steps_roof,
+        "board_power": power.summary(),
         "steps_ms": {k: v[0] for k, v in table.items() if v[1] > 0},
         "workload": "%s: %d layers, D=%d, %dx%d heads, MLP %d, patch %d x temporal %d, %d items, %d attention segments, %d patch tokens -> %d visual tokens"
                     % (cfg.name, cfg.num_layers, cfg.hidden, cfg.num_heads, cfg.head_dim, cfg.mlp_dim, cfg.patch, cfg.temporal_patch,
@@ -287,7 +339,8 @@ def summary_block(res):
     return {"workload": res["workload"], "value": res["value"], "unit": "visual tokens/s", "ms_per_step": res["ms_per_step"],
             "patch_tokens_per_s": res["T"] / (res["ms_per_step"] * 1e-3), "tflops_end_to_end": res["tflops"],
             "mfma_util_pct_end_to_end": 100 * res["tflops"] / PEAK_BF16_TFLOPS, "attention_flop_share": res["attention_flop_share"],
-            "roofline": res["roofline"], "rooflines_per_step": res["rooflines_per_step"], "steps_ms": res["steps_ms"]}
+            "roofline": res["roofline"], "rooflines_per_step": res["rooflines_per_step"], "steps_ms": res["steps_ms"],
+            "board_power": res["board_power"]}
 
 
 def preprocess_and_store(res, with_store):
@@ -467,21 +520,28 @@ def mfma_peak():
     from paper_2601_11590_amd import binding as B
     out = torch.zeros(256 * 512, dtype=torch.float32, device="cuda:0")
     st = torch.cuda.current_stream().cuda_stream
-    res = {}
+    res, watts = {}, {}
     for shape, sname in ((0, "v_mfma_f32_32x32x16_bf16"), (1, "v_mfma_f32_16x16x32_bf16")):
         for zero in (False, True):
             B.epd_probe_mfma_rate(shape, zero, 200, out.data_ptr(), st)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            fl = B.epd_probe_mfma_rate(shape, zero, 20000, out.data_ptr(), st)
-            e1.record()
-            torch.cuda.synchronize()
-            tf = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
-            res["%s, %s operands" % (sname, "all-zero" if zero else "random")] = tf
-            log("[mfma-peak] %-28s %-8s operands: %7.1f TFLOP/s (%.1f%% of %.0f)" % (sname, "all-zero" if zero else "random", tf, 100 * tf / PEAK_BF16_TFLOPS, PEAK_BF16_TFLOPS))
+            reps = 300       # 6 - 8 s per case: the power sensor settles within the first second
+            with PowerSampler() as power:
+                e0.record()
+                for _ in range(reps):
+                    fl = B.epd_probe_mfma_rate(shape, zero, 20000, out.data_ptr(), st)
+                e1.record()
+                torch.cuda.synchronize()
+            tf = reps * fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            pw = power.summary(tail=0.75)
+            key = "%s, %s operands" % (sname, "all-zero" if zero else "random")
+            res[key] = tf
+            watts[key] = pw
+            log("[mfma-peak] %-28s %-8s operands: %7.1f TFLOP/s (%.1f%% of %.0f)%s" % (sname, "all-zero" if zero else "random", tf, 100 * tf / PEAK_BF16_TFLOPS, PEAK_BF16_TFLOPS,
+                                                                                       "  board power %.0f W of %.0f" % (pw["mean_w"], pw["cap_w"] or 0) if pw else ""))
     print(json.dumps({"experiment": "bf16 matrix-core rate on register-resident operands, 2 waves per SIMD on all 256 CUs, TFLOP/s",
-                      "published_peak": PEAK_BF16_TFLOPS, "measured": res}), flush=True)
+                      "published_peak": PEAK_BF16_TFLOPS, "measured": res, "board_power": watts}), flush=True)
 
 
 def main():
@@ -563,6 +623,7 @@ def main():
         "preprocess": prep,
         "mm_store": store_res,
         "steps_ms": head["steps_ms"],
+        "board_power": head["board_power"],
         "peaks": {"bf16_mfma_TFLOPs": PEAK_BF16_TFLOPS, "hbm_GBs": PEAK_HBM_GBS},
     }
     release(head)
