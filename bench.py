@@ -7,8 +7,8 @@ video encoder (hidden 3200, 25 heads x 128, MLP 12800, patch 14 x temporal 2, 3-
 four clips of 16 frames at 448 x 448 -- 32 768 packed patch tokens -> 8192 visual tokens.  One
 "step" is one epd_encode call: plan, patch embedding, all transformer blocks, final norm, 2x2
 merge and projection, with the packed patches and weights already resident in HBM.  The other
-bf16 configurations (C2, C3, C4) are timed in the same run, briefly, and reported in the
-"others" block of the line.
+bf16 configurations (C2, C3, C4) and the batch of the paper's Table 4_2 resolutions (T42) are
+timed in the same run, briefly, and reported in the "others" block of the line.
 
 Prints ONE JSON line on stdout; progress and the per-step tables go to stderr.
 """
@@ -552,7 +552,7 @@ def main():
     ap.add_argument("--config", default="C5", help="headline workload: C5 (default, the largest single-GPU configuration) | C2 | C3 | C4 | "
                          "T42 (the six image resolutions of the paper's Table 4_2 as one batch)")
     ap.add_argument("--others", default=None,
-                    help="comma-separated configurations timed briefly beside the headline (default: C2,C3,C4 with C5, none otherwise; '' = none)")
+                    help="comma-separated configurations timed briefly beside the headline (default: C2,C3,C4,T42 with C5, none otherwise; '' = none)")
     ap.add_argument("--layers", type=int, default=None, help="override depth (experiments only; never the headline)")
     ap.add_argument("--segments", default="item", choices=["item", "frame"],
                     help="attention segments: one per image / clip (default) or one per video frame (windowed attention)")
@@ -629,10 +629,10 @@ def main():
     release(head)
     others = args.others
     if others is None:
-        others = "C2,C3,C4" if (args.config == "C5" and plain) else ""
+        others = "C2,C3,C4,T42" if (args.config == "C5" and plain) else ""
     blocks = {}
     for name in [n for n in others.split(",") if n]:
-        r = measure(name, 5, 2)
+        r = measure(name, 3 if name == "T42" else 5, 1 if name == "T42" else 2)
         blocks[name] = summary_block(r)
         if name in ("C4",):
             blocks[name]["parity_vs_stored_oracle_rows"] = stored_rows_parity(name, r["out"].float().cpu().numpy())
