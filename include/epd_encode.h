@@ -269,8 +269,9 @@ epd_status epd_encode_debug_hidden(epd_handle h, void* out_T_by_D_f32, void* str
  * of this handle (ignored by the fp32 path).
  *   gemm_tile    -1 = the library's choice per GEMM; 0 (256x256), 2 (256x128), 4 (128x128) or
  *                5 (320x256) = that output tile for every GEMM that can take it
- *   attn_groups  0 = the library's choice; 1 or 2 = 32-row query groups per wave of the attention
- *                kernel (2 exists for head_dim <= 64 only: EPD_ERR_UNSUPPORTED otherwise)
+ *   attn_groups  0 = the library's choice; 1 = 128, 2 = 256 query rows per block of the attention
+ *                kernel (256: two 32-row groups per wave for head_dim <= 64, eight waves of one
+ *                group for larger head dims); EPD_ERR_UNSUPPORTED where a setting has no kernel
  * Any other value returns EPD_ERR_INVALID_ARG and changes nothing.  Results stay within the
  * stated tolerances under every setting; they are bit-identical only under the same setting. */
 epd_status epd_encode_set_tuning(epd_handle h, int32_t gemm_tile, int32_t attn_groups);

@@ -3,8 +3,8 @@
 // the visual sequence length (paper section 1).  O = softmax(Q K^T / sqrt(d)) V per segment
 // and head, never materialising the score matrix.
 //
-// Layout of the computation (one block = 4 waves = one tile of query rows of one segment and
-// head; a wave owns NQ groups of 32 query rows):
+// Layout of the computation (one block = NW waves (4 or 8) = one tile of query rows of one
+// segment and head; a wave owns NQ groups of 32 query rows):
 //   * Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: a lane then
 //     holds ONE query column (lane % 32) and 16 key rows per 32x32 tile, so the running
 //     maximum and the running sum of the softmax are per-lane scalars; one exchange between
@@ -89,8 +89,9 @@ __device__ __forceinline__ float half_swap_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int DH, int NQ, int MINBLK, bool SUMROW>
-__global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
+template <int DH, int NQ, int MINBLK, bool SUMROW, int NW>
+__global__ __launch_bounds__(64 * NW, MINBLK) void attn_bf16_kernel(AttnArgs a) {
+  constexpr int NT = 64 * NW;              // threads per block
   constexpr int KS = (DH + 15) / 16;       // k-steps of the score GEMM
   constexpr int DB = (DH + 31) / 32;       // 32-row blocks of O^T that hold output channels
   // SUMROW: row DH of the V^T tile in LDS is a row of ones, so that row DH of O^T accumulates
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   constexpr int KBYTES = BKV * ROWK;
   constexpr int VBYTES = VROWS * 128;      // V^T tile: DH rows of 64 keys, padded to whole blocks of rows
   constexpr int STAGE = KBYTES + VBYTES;
-  constexpr int LK = (BKV * CPRK + 255) / 256, LV = (DH * 8 + 255) / 256;
+  constexpr int LK = (BKV * CPRK + NT - 1) / NT, LV = (DH * 8 + NT - 1) / NT;
   // K row swizzle: power-of-two rows need one (all rows would start in the same banks);
   // 144-byte rows (d = 72) already spread 16 consecutive rows over all 64 banks
   constexpr bool SWZK = (CPRK & (CPRK - 1)) == 0;
@@ -138,7 +139,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   // (SUMROW), the others zero, once, before the first barrier
   if constexpr (VROWS > DH) {
     constexpr int PADCH = (VROWS - DH) * 8;      // 16-byte chunks per stage
-    for (int i = threadIdx.x; i < 2 * PADCH; i += 256) {
+    for (int i = threadIdx.x; i < 2 * PADCH; i += NT) {
       const int st = i / PADCH, ch = i - st * PADCH;
       const uint32_t fill = (SUMROW && ch < 8) ? 0x3F803F80u : 0u;   // bf16 1.0 pairs
       *(uint4*)(lds + st * STAGE + KBYTES + DH * 128 + ch * 16) = make_uint4(fill, fill, fill, fill);
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   bool k_on[LK];
 #pragma unroll
   for (int it = 0; it < LK; ++it) {
-    const int lin = it * 256 + tid;
+    const int lin = it * NT + tid;
     k_on[it] = lin < BKV * CPRK;
     const int row = lin / CPRK, slot = lin - row * CPRK;
     k_row[it] = key_of_row(row);   // LDS row `row` receives this key of the tile
@@ -160,7 +161,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   bool v_on[LV];
 #pragma unroll
   for (int it = 0; it < LV; ++it) {
-    const int lin = it * 256 + tid;
+    const int lin = it * NT + tid;
     v_on[it] = lin < DH * 8;
     const int row = lin >> 3, slot = lin & 7;
     v_off[it] = (uint32_t)row * (uint32_t)a.vt_stride * 2u + (uint32_t)((slot ^ ((row >> 1) & 7)) * 16);
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
         // scalar base + 32-bit lane offset: the load's own addressing form, no 64-bit vector
         // arithmetic (a segment's K rows span far less than 4 GB)
         const uint32_t off = (uint32_t)r * (uint32_t)(a.ld_qkv * 2) + (uint32_t)(k_ch[it] * 16);
-        __builtin_amdgcn_global_load_lds(EPD_GPTR(kbase + (size_t)off), EPD_LPTR(sb + (it * 256 + wave * 64) * 16), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(EPD_GPTR(kbase + (size_t)off), EPD_LPTR(sb + (it * NT + wave * 64) * 16), 16, 0, 0);
       }
     }
     const char* vb = vbase + (size_t)kv0 * 2;
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
       if (v_on[it]) {
         uint32_t off = v_off[it];
         asm volatile("" : "+v"(off));        // keeps the widening to 64 bits next to the load (same form as above)
-        __builtin_amdgcn_global_load_lds(EPD_GPTR(vb + (size_t)off), EPD_LPTR(sb + KBYTES + (it * 256 + wave * 64) * 16), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(EPD_GPTR(vb + (size_t)off), EPD_LPTR(sb + KBYTES + (it * NT + wave * 64) * 16), 16, 0, 0);
       }
     }
   };
@@ -513,14 +514,18 @@ __global__ __launch_bounds__(256, MINBLK) void attn_bf16_kernel(AttnArgs a) {
   }
 }
 
-// Query rows per work item.  Two 32-row groups per wave (256-row tiles) halve the LDS
-// fragment traffic per MFMA and win for d <= 64 on long segments; otherwise one group per
-// wave (128-row tiles) wastes less on segment tails.  The one-group kernels for d <= 64 are
-// compiled for four waves per SIMD (128 registers, which the compiler meets with one spilled
-// register): +6-10 % over three, and a batch of eight 784-token images x 16 heads (3200 wave
-// tasks) then fits the chip's 4096 wave slots in one round.
-static int bf16_nq(int head_dim, int max_seg_len) {
-  return (head_dim <= 64 && max_seg_len > 1024) ? 2 : 1;
+// Query rows per work item: 128 (four waves of one 32-row group) or 256.  For d <= 64 the 256-row
+// tile is four waves of TWO groups each, which halves the LDS fragment traffic per MFMA and wins
+// on long segments; the one-group kernels for d <= 64 are compiled for four waves per SIMD (128
+// registers, which the compiler meets with one spilled register): +6-10 % over three, and a batch
+// of eight 784-token images x 16 heads (3200 wave tasks) then fits the chip's 4096 wave slots in
+// one round.  Larger head dims have no registers for two groups per wave at two waves per SIMD;
+// their 256-row tile is EIGHT waves of one group -- one block per compute unit instead of two, so
+// every K / V^T tile is loaded once for 256 query rows: +4 % at d = 72 on a 28 224-token segment,
+// nothing at d = 128 (where it is kept for tuning and tests only).  Short segments keep the
+// 128-row tile, which wastes less on their tails.
+static int bf16_q_rows(int head_dim, int max_seg_len) {
+  return (head_dim < 128 && max_seg_len > 1024) ? 256 : 128;
 }
 
 int attn_q_tile(bool bf16, int head_dim, int max_seg_len, int groups) {
@@ -530,29 +535,31 @@ int attn_q_tile(bool bf16, int head_dim, int max_seg_len, int groups) {
       default: return 0;
     }
   }
-  if (groups < 0 || groups > 2 || (groups == 2 && head_dim > 64)) return 0;
+  if (groups < 0 || groups > 2) return 0;
   switch (head_dim) {
     case 32: case 64: case 72: case 80: case 96: case 128:
-      return 128 * (groups ? groups : bf16_nq(head_dim, max_seg_len));
+      return groups ? 128 * groups : bf16_q_rows(head_dim, max_seg_len);
     default: return 0;
   }
 }
 
 bool launch_attn_bf16(const AttnArgs& a, hipStream_t s) {
   if (a.num_work <= 0) return true;
-  dim3 grid(a.num_work * a.num_heads), block(256);
-  const int nq = a.q_tile / 128;
+  if (a.q_tile != 128 && a.q_tile != 256) return false;
+  const bool wide = a.q_tile == 256;
+  dim3 grid(a.num_work * a.num_heads);
   // The row of ones is used where the head dim leaves spare rows in its last 32-row block of
   // O^T (d = 72, 80: +3 % measured); for d = 32, 64, 96, 128 it would add a block of matrix
   // instructions and measured 2-7 % slower.
 #define EPD_ATTN(DH)                                                                                     \
   case DH: {                                                                                             \
     constexpr bool sr = (DH % 32) != 0;                                                                  \
-    if constexpr (DH <= 64) {                                                                            \
-      if (nq == 2) { hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, 2, sr>), grid, block, 0, s, a); return true; } \
+    if (wide) {                                                                                          \
+      if constexpr (DH <= 64) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, 2, sr, 4>), grid, dim3(256), 0, s, a); \
+      else hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, 1, sr, 8>), grid, dim3(512), 0, s, a);          \
+    } else {                                                                                             \
+      hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, (DH <= 64 ? 4 : 2), sr, 4>), grid, dim3(256), 0, s, a); \
     }                                                                                                    \
-    if (nq != 1) return false;                                                                           \
-    hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, (DH <= 64 ? 4 : 2), sr>), grid, block, 0, s, a);        \
     return true;                                                                                         \
   }
   switch (a.head_dim) {

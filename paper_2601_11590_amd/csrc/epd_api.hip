@@ -230,7 +230,7 @@ struct epd_encoder {
   // timing
   // tuning hook (epd_encode_set_tuning): 0 = the library's own choice
   int tile_cfg = 0;      // k > 0: bf16 GEMM tile variant k - 1
-  int attn_groups = 0;   // 1 or 2: 32-row query groups per wave of the bf16 attention kernel
+  int attn_groups = 0;   // 1 or 2: 128 or 256 query rows per block of the bf16 attention kernel
   int timed_step = -1;
   std::vector<hipEvent_t> ev;     // pairs (start, stop), created lazily
   int ev_used = 0;

@@ -83,7 +83,7 @@ struct AttnArgs {
   int num_heads, head_dim;
   float scale;          // 1 / sqrt(head_dim); fp32 path only -- the bf16 path expects Q already
                         //   multiplied by scale * log2(e) (GemmArgs::q_scale)
-  int q_tile;           // query rows per work item (attn_q_tile of this call)
+  int q_tile;           // query rows per work item (attn_q_tile of this call: 128 or 256 on the bf16 path)
 };
 
 // ---------------------------------------------------------------- plan (per-call metadata)
@@ -120,8 +120,8 @@ void plan_gemm_bf16(const GemmArgs& g, int compute_units, int* tile_rows, int* t
 bool launch_attn_bf16(const AttnArgs& a, hipStream_t s);  // false: head_dim not covered
 // query rows per work item for segments up to max_seg_len (0 = unsupported head_dim);
 // never smaller than attn_q_tile(bf16, head_dim, 1).  groups: 0 = the library's choice; 1 or 2 =
-// that many 32-row groups per wave on the bf16 path (2 exists for head_dim <= 64 only; 0 is
-// returned where the request has no kernel)
+// 128 or 256 query rows per work item on the bf16 path (256 = two 32-row groups per wave for
+// head_dim <= 64, eight waves of one group above; 0 is returned where the request has no kernel)
 int attn_q_tile(bool bf16, int head_dim, int max_seg_len, int groups = 0);
 // W[n][k] *= gamma[k] (bf16, in place): folds the scale of an RMSNorm into the weights of the
 // linear layer that consumes its output, so that  (x * rstd * gamma) W^T = rstd * (x (W gamma)^T)

@@ -21,11 +21,14 @@ tolerances (per-token cosine >= 0.999, max-norm relative error <= 2e-2):
            tiles underflow) or late (last key tile: the reference jumps by ~ 200 log2 units and
            everything accumulated before is scaled to 0).
 
-Variants (template arguments <head dim, 32-row groups per wave, blocks per CU, ones row>):
-  <32,1,4,0> <64,1,4,0>   d <= 64, segments <= 1024: reference subtracted per score, VALU sum
-  <32,2,2,0> <64,2,2,0>   d <= 64, a segment > 1024: two groups per wave, per-group alpha
-  <72,1,2,1> <80,1,2,1>   accumulator-preset reference (CREF) + ones-row denominator (SUMROW)
-  <96,1,2,0> <128,1,2,0>  accumulator-preset reference, VALU sum
+Variants (template arguments <head dim, 32-row groups per wave, blocks per CU, ones row, waves per block>):
+  <32,1,4,0,4> <64,1,4,0,4>   d <= 64, segments <= 1024: reference subtracted per score, VALU sum
+  <32,2,2,0,4> <64,2,2,0,4>   d <= 64, a segment > 1024: two groups per wave, per-group alpha
+  <72,1,2,1,4> <80,1,2,1,4>   accumulator-preset reference (CREF) + ones-row denominator (SUMROW);
+                              d = 72 with its last channels and the ones row as a 16-row block
+  <96,1,2,0,4> <128,1,2,0,4>  accumulator-preset reference, VALU sum
+  <72|80|96|128,1,1,*,8>      the same four with eight waves per block (256 query rows; chosen by the
+                              library for 64 < d < 128 when a segment is longer than 1024 tokens)
 """
 
 import numpy as np
@@ -135,19 +138,30 @@ def test_sharp_softmax_two_groups_forced_on_short_segments(d):
     sharp_case(d, SHORT, attn_groups=2)
 
 
+@pytest.mark.parametrize("rows", [128, 256])
 @pytest.mark.parametrize("d", [72, 80])
-def test_sharp_softmax_preset_reference_and_ones_row(d):
-    # attn_bf16_kernel<d,1,2,true>: CREF (scores accumulate onto the preset -reference; when a
-    # row moves, delta = mx is subtracted, o *= alpha and the preset is renewed from mrun) and
-    # SUMROW (row d of O^T accumulates the denominator and is rescaled with the outputs)
-    sharp_case(d, LONG, norm="layernorm")
+def test_sharp_softmax_preset_reference_and_ones_row(d, rows):
+    # attn_bf16_kernel<d,1,2,true,4> (128 query rows per block) and <d,1,1,true,8> (256): CREF
+    # (scores accumulate onto the preset -reference; when a row moves, delta = mx is subtracted,
+    # o *= alpha and the preset is renewed from mrun) and SUMROW (row d of O^T accumulates the
+    # denominator and is rescaled with the outputs; at d = 72 in the 16-row block, whose rescale
+    # factors and denominators cross lanes by v_permlane16_swap)
+    sharp_case(d, LONG, attn_groups=rows // 128, norm="layernorm")
 
 
+@pytest.mark.parametrize("rows", [128, 256])
 @pytest.mark.parametrize("d", [96, 128])
-def test_sharp_softmax_preset_reference_vector_sum(d):
-    # attn_bf16_kernel<d,1,2,false>: CREF with the denominator kept per lane
+def test_sharp_softmax_preset_reference_vector_sum(d, rows):
+    # attn_bf16_kernel<d,1,2,false,4> and <d,1,1,false,8>: CREF with the denominator kept per lane
     # (lrun = lrun * alpha + psum) and merged across the wave halves at the end
-    sharp_case(d, LONG, rope="3d", rope_pairs=(d // 8, d // 4 - d // 8, d // 4))
+    sharp_case(d, LONG, attn_groups=rows // 128, rope="3d", rope_pairs=(d // 8, d // 4 - d // 8, d // 4))
+
+
+@pytest.mark.parametrize("d", [72, 128])
+def test_sharp_softmax_eight_waves_forced_on_short_segments(d):
+    # the 256-row tile on segments whose last query tile is mostly empty (76 of 256 rows): five
+    # of the eight waves have no query row and only load and synchronise
+    sharp_case(d, SHORT, attn_groups=2)
 
 
 @pytest.mark.parametrize("d", [64, 72, 128])

@@ -224,7 +224,7 @@ def test_tuning_hook_rejects_what_has_no_kernel_and_keeps_the_result_within_tole
     enc, gw, layers = make_encoder(cfg, 512)
     try:
         for tile, groups, status in ((3, 0, B.EPD_ERR_INVALID_ARG), (-2, 0, B.EPD_ERR_INVALID_ARG), (0, 3, B.EPD_ERR_INVALID_ARG),
-                                     (-1, 2, B.EPD_ERR_UNSUPPORTED)):      # two query groups exist for head_dim <= 64 only
+                                     (1, 0, B.EPD_ERR_INVALID_ARG), (-1, -1, B.EPD_ERR_INVALID_ARG)):
             with pytest.raises(B.EpdError) as ei:
                 enc.set_tuning(tile, groups)
             assert ei.value.status == status, str(ei.value)
