@@ -316,15 +316,16 @@ epd_status epd_probe_mfma_rate(int32_t shape, int32_t zero_operands, int32_t ite
                                float* device_out, double* flops_per_launch, void* stream);
 
 /* Host only, launches nothing: how the bf16 GEMM of the encoder layers would tile an M x N
- * output (tokens x output columns) on a chip of `compute_units` units (<= 0: the current
- * device's, 256 where there is none).  The layer GEMMs of V_m = E(I_m) (section 3.1, Eq. 1) run
- * as one launch of tile_rows x tile_cols tiles, or -- body_rows > 0 -- as that launch over the
- * first body_rows tokens plus a second launch of 128 x 128 tiles over the rest, which turns a
- * partial last round of large tiles into a round of small ones.
- *   qkv_epilogue  1 = the QKV projection (Q | K columns [0, qk_cols), then V), 0 = any other
- * All three outputs are HOST pointers.  EPD_ERR_INVALID_ARG on M, N <= 0, a NULL output, or
- * qk_cols outside (0, N] with qkv_epilogue set. */
-epd_status epd_probe_gemm_plan(int32_t M, int32_t N, int32_t qkv_epilogue, int32_t qk_cols,
+ * output (tokens x output columns) with inner dimension K on a chip of `compute_units` units
+ * (<= 0: the current device's, 256 where there is none).  The layer GEMMs of V_m = E(I_m)
+ * (section 3.1, Eq. 1) run as one launch of tile_rows x tile_cols tiles, or -- body_rows > 0 --
+ * as that launch over the first body_rows tokens plus a second launch of 128 x 128 tiles over the
+ * rest, which turns a partial last round of large tiles into a round of small ones.
+ *   epilogue  0 = store, 1 = GELU (first MLP GEMM), 2 = residual add (attention output projection,
+ *             second MLP GEMM), 3 = the QKV projection (Q | K columns [0, qk_cols), then V)
+ * All three outputs are HOST pointers.  EPD_ERR_INVALID_ARG on M, N, K <= 0, an epilogue outside
+ * 0 .. 3, a NULL output, or qk_cols outside (0, N] with epilogue 3. */
+epd_status epd_probe_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t qk_cols,
                                int32_t compute_units, int32_t* tile_rows, int32_t* tile_cols,
                                int32_t* body_rows);
 

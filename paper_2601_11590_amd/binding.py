@@ -107,7 +107,7 @@ def _load() -> C.CDLL:
     lib.epd_probe_mfma_rate.restype = C.c_int
     lib.epd_probe_mfma_rate.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
     lib.epd_probe_gemm_plan.restype = C.c_int
-    lib.epd_probe_gemm_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)] * 3
+    lib.epd_probe_gemm_plan.argtypes = [C.c_int32] * 6 + [C.POINTER(C.c_int32)] * 3
     lib.epd_encode_set_tuning.restype = C.c_int
     lib.epd_encode_set_tuning.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
     lib.epd_encode_get_timing.restype = C.c_int
@@ -507,10 +507,13 @@ def to_device_patches(patches_f32: np.ndarray, dtype: str, device: str = "cuda:0
     return torch.from_numpy(np.ascontiguousarray(patches_f32)).to(device).to(torch_dtype(dtype)).contiguous()
 
 
-def epd_probe_gemm_plan(M: int, N: int, qkv_epilogue: bool = False, qk_cols: int = 0, compute_units: int = 0):
-    """(tile_rows, tile_cols, body_rows) of the layer GEMM's launch plan for an M x N output (host only)."""
+EPI_STORE, EPI_GELU, EPI_RESIDUAL, EPI_QKV = 0, 1, 2, 3
+
+
+def epd_probe_gemm_plan(M: int, N: int, K: int, epilogue: int = EPI_STORE, qk_cols: int = 0, compute_units: int = 0):
+    """(tile_rows, tile_cols, body_rows) of the layer GEMM's launch plan for an M x N x K product (host only)."""
     tr, tc, br = C.c_int32(), C.c_int32(), C.c_int32()
-    st = lib.epd_probe_gemm_plan(M, N, 1 if qkv_epilogue else 0, qk_cols, compute_units, C.byref(tr), C.byref(tc), C.byref(br))
+    st = lib.epd_probe_gemm_plan(M, N, K, epilogue, qk_cols, compute_units, C.byref(tr), C.byref(tc), C.byref(br))
     if st != EPD_OK:
         raise EpdError(st, "epd_probe_gemm_plan: bad argument")
     return tr.value, tc.value, br.value

@@ -822,23 +822,33 @@ using T4 = Tile<128, 128, 64, 2, 2, 2, 4>;   // 4 waves, 64x64 wave tiles, 64 KB
 using T5 = Tile<320, 256, 64, 2, 4, 1, 5>;   // 8 waves, 160x64 wave tiles, 144 KB LDS, one block per CU
 
 // Tile choice.  Both large tiles run one block per compute unit, so an output whose number of
-// tiles is not a multiple of the unit count pays a whole tile time for its last, partial round.
-// The 128 x 128 tile runs two blocks per unit (the epilogue of one hides behind the main loop of
-// the other) and quantises four times finer, at 0.87 of the rate per unit of output area.  The
-// 320 x 256 tile moves the fewest operand bytes per flop; launched alone in a loop it is 5 - 9 %
-// faster than the 256 x 256 tile, but inside an encoder call -- where the chip sits at its power
-// limit from the first layer to the last -- the two measured equal on every GEMM of the largest
-// configuration, so it is priced at the same rate and wins only where it needs fewer rounds
-// (a 6272 x 3072 output is 240 of its tiles: one round on 256 units instead of two).  A launch is
-// priced by the output area its busiest compute unit works through -- rounds of blocks x blocks
-// per unit x tile area -- over that relative rate.
-struct TileShape { int bm, bn, blocks, cfg; double rate; };
-constexpr TileShape kShape256 = {256, 256, 1, 0, 1.0}, kShape320 = {320, 256, 1, 5, 1.0}, kShape128 = {128, 128, 2, 4, 0.87};
+// tiles is not a multiple of the unit count pays a whole tile time for its last, partial round,
+// and nothing hides their epilogues.  The 128 x 128 tile runs two blocks per unit (the epilogue of
+// one hides behind the main loop of the other) and quantises four times finer, but its main loop
+// is the slowest.  The 320 x 256 tile moves the fewest operand bytes per flop.  A launch is priced
+// by a model fitted to launch times measured INSIDE encoder calls (where the chip sits at its
+// power limit; loops of one GEMM alone rank the tiles differently): the time of one round of
+// blocks is, per 256 x 256 of output area,  alpha * K / 1024 + eps[epilogue]  microseconds
+// (32768-token and 73896-token batches, K = 1024 ... 12800; it reproduces the measured launches
+// of the 6272-token batch as well):
+//                  alpha   eps: store / GELU   residual add   QKV + rotary
+//   256 x 256      22.6        13.2               39.4            21.9
+//   320 x 256      21.8        11.7               39.4            24.8
+//   128 x 128      32.8         4.6               23.8            19.6
+// So the small tile wins short-K GEMMs with a heavy epilogue (the attention output projection at
+// hidden 1024), the 320 x 256 tile gains with short K and on grids where it needs fewer rounds,
+// and at K >= 3200 the two large tiles are equal.
+struct TileShape { int bm, bn, blocks, cfg; double alpha, eps[4]; };   // eps indexed by Epilogue
+constexpr TileShape kShape256 = {256, 256, 1, 0, 22.6, {13.2, 13.2, 39.4, 21.9}};
+constexpr TileShape kShape320 = {320, 256, 1, 5, 21.8, {11.7, 11.7, 39.4, 24.8}};
+constexpr TileShape kShape128 = {128, 128, 2, 4, 32.8, {4.6, 4.6, 23.8, 19.6}};
+constexpr double kSecondLaunch = 4.0;      // what a second launch of the same GEMM adds (gap + ramp), same unit
 
-static double tile_cost(int M, int N, const TileShape& t, long cus) {
+static double tile_cost(int M, int N, int K, int epi, const TileShape& t, long cus) {
   const long tiles = (long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
   const long slots = cus * t.blocks;
-  return (double)((tiles + slots - 1) / slots) * t.blocks * t.bm * t.bn / t.rate;
+  const double per_round = (double)t.blocks * t.bm * t.bn / 65536.0 * (t.alpha * K / 1024.0 + t.eps[epi & 3]);
+  return (double)((tiles + slots - 1) / slots) * per_round;
 }
 
 // How to cover an M x N output: one launch of `tile`, or (body_rows > 0) the first body_rows rows
@@ -848,14 +858,14 @@ static double tile_cost(int M, int N, const TileShape& t, long cus) {
 // rounds, priced 7; cut after 30208 rows it is 6 rounds plus 500 small tiles.
 struct TilePlan { int tile, body_rows; double cost; };
 
-static TilePlan plan_tiles(int M, int N, bool may_split, long cus) {
-  TilePlan best = {0, 0, tile_cost(M, N, kShape256, cus)};
+static TilePlan plan_tiles(int M, int N, int K, int epi, bool may_split, long cus) {
+  TilePlan best = {0, 0, tile_cost(M, N, K, epi, kShape256, cus)};
   const double keep = 0.97 * best.cost;          // the plain 256 x 256 launch stays unless clearly beaten
   auto offer = [&](int tile, int body_rows, double cost) {
     if (cost < keep && cost < best.cost) best = {tile, body_rows, cost};
   };
-  offer(kShape128.cfg, 0, tile_cost(M, N, kShape128, cus));
-  offer(kShape320.cfg, 0, tile_cost(M, N, kShape320, cus));
+  offer(kShape128.cfg, 0, tile_cost(M, N, K, epi, kShape128, cus));
+  offer(kShape320.cfg, 0, tile_cost(M, N, K, epi, kShape320, cus));
   if (may_split) {
     for (const TileShape* t : {&kShape256, &kShape320}) {
       const long tm = (M + t->bm - 1) / t->bm, tn = (N + t->bn - 1) / t->bn;
@@ -864,7 +874,7 @@ static TilePlan plan_tiles(int M, int N, bool may_split, long cus) {
       const long body_tm = std::min(full * cus / tn, (long)(M / t->bm));   // whole row tiles within them
       if (body_tm < 1 || body_tm * t->bm >= M) continue;
       const int body_rows = (int)body_tm * t->bm;
-      offer(t->cfg, body_rows, tile_cost(body_rows, N, *t, cus) + tile_cost(M - body_rows, N, kShape128, cus));
+      offer(t->cfg, body_rows, tile_cost(body_rows, N, K, epi, *t, cus) + tile_cost(M - body_rows, N, K, epi, kShape128, cus) + kSecondLaunch);
     }
   }
   return best;
@@ -873,7 +883,7 @@ static TilePlan plan_tiles(int M, int N, bool may_split, long cus) {
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
   int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1;   // tile_cfg: set by the tuning hook of the C ABI, or by a split
-  if (t != 0 && t != 2 && t != 4 && t != 5) t = plan_tiles(g.M, g.N, false, num_cus()).tile;
+  if (t != 0 && t != 2 && t != 4 && t != 5) t = plan_tiles(g.M, g.N, g.K, g.epilogue, false, num_cus()).tile;
   if (EPI == EPI_QKV && (t == 0 || t == 5) && g.qk_cols % 256 != 0) t = 2;
   switch (t) {
     case 0: launch_cfg<T0, EPI, OUT, GATHER>(g, s); break;
@@ -897,7 +907,7 @@ void plan_gemm_bf16(const GemmArgs& g, int compute_units, int* tile_rows, int* t
   const long cus = compute_units > 0 ? compute_units : num_cus();
   int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1, body = 0;
   if (t != 0 && t != 2 && t != 4 && t != 5) {
-    const TilePlan p = plan_tiles(g.M, g.N, may_split_rows(g), cus);
+    const TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue, may_split_rows(g), cus);
     t = p.tile; body = p.body_rows;
   }
   if (g.epilogue == EPI_QKV && (t == 0 || t == 5) && g.qk_cols % 256 != 0) t = 2;
@@ -908,7 +918,7 @@ void plan_gemm_bf16(const GemmArgs& g, int compute_units, int* tile_rows, int* t
 
 void launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
-  const TilePlan plan = may_split_rows(g) ? plan_tiles(g.M, g.N, true, num_cus()) : TilePlan{0, 0, 0.0};
+  const TilePlan plan = may_split_rows(g) ? plan_tiles(g.M, g.N, g.K, g.epilogue, true, num_cus()) : TilePlan{0, 0, 0.0};
   if (plan.body_rows <= 0) { launch_gemm_bf16_whole(g, s); return; }
   const int mb = plan.body_rows;
   GemmArgs body = g, tail = g;

@@ -101,15 +101,16 @@ extern "C" epd_status epd_probe_stream_read(const void* device_buf, uint64_t byt
   return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
 }
 
-// Host only: the tiling launch_gemm_bf16 chooses for an M x N output (see plan_gemm_bf16).
-extern "C" epd_status epd_probe_gemm_plan(int32_t M, int32_t N, int32_t qkv_epilogue, int32_t qk_cols, int32_t compute_units,
+// Host only: the tiling launch_gemm_bf16 chooses for an M x N x K GEMM (see plan_gemm_bf16).
+extern "C" epd_status epd_probe_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t qk_cols, int32_t compute_units,
                                           int32_t* tile_rows, int32_t* tile_cols, int32_t* body_rows) {
-  if (M <= 0 || N <= 0 || !tile_rows || !tile_cols || !body_rows || (qkv_epilogue && (qk_cols <= 0 || qk_cols > N)))
+  if (M <= 0 || N <= 0 || K <= 0 || epilogue < 0 || epilogue > 3 || !tile_rows || !tile_cols || !body_rows ||
+      (epilogue == epd::EPI_QKV && (qk_cols <= 0 || qk_cols > N)))
     return EPD_ERR_INVALID_ARG;
   epd::GemmArgs g{};
-  g.M = M; g.N = N;
-  g.epilogue = qkv_epilogue ? epd::EPI_QKV : epd::EPI_STORE;
-  g.qk_cols = qkv_epilogue ? qk_cols : 0;
+  g.M = M; g.N = N; g.K = K;
+  g.epilogue = epilogue;
+  g.qk_cols = epilogue == epd::EPI_QKV ? qk_cols : 0;
   int tr = 0, tc = 0, br = 0;
   epd::plan_gemm_bf16(g, compute_units, &tr, &tc, &br);
   *tile_rows = tr; *tile_cols = tc; *body_rows = br;

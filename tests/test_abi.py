@@ -213,24 +213,33 @@ def test_workspace_pads_mlp_width_and_keeps_a_read_tail():
 def test_gemm_launch_planner_on_the_benchmark_shapes():
     """Host logic of the bf16 GEMM launcher, read through its probe for a 256-unit chip: one
     launch of a large tile where its rounds come out whole, the 320 x 256 tile where it saves a
-    round, 128 x 128 tiles on narrow outputs, and a large-tile body plus a small-tile tail where
-    the last round of large tiles would be partial."""
+    round or K is short, 128 x 128 tiles on narrow outputs and for short-K GEMMs with a heavy
+    epilogue, and a large-tile body plus a small-tile tail where the last round of large tiles
+    would be partial."""
     from paper_2601_11590_amd import binding as B
     plan = lambda *a: B.epd_probe_gemm_plan(*a, compute_units=256)
+    G, R, Q = B.EPI_GELU, B.EPI_RESIDUAL, B.EPI_QKV
     # C5 (32 768 tokens, hidden 3200, MLP 12 800): fc1 = 6400 tiles = 25 whole rounds, QKV = 19
-    assert plan(32768, 12800) == (256, 256, 0)
-    assert plan(32768, 9600, True, 6400) == (256, 256, 0)
+    assert plan(32768, 12800, 3200, G) == (256, 256, 0)
+    assert plan(32768, 9600, 3200, Q, 6400) == (256, 256, 0)
     # ... proj / fc2: 1664 tiles = 6.5 rounds -> 6 rounds over 30 208 rows + small tiles
-    assert plan(32768, 3200) == (256, 256, 30208)
-    # C2 (6272 tokens, hidden 1024): QKV is ONE round of 240 320 x 256 tiles; N = 1024 -> 128 x 128
-    assert plan(6272, 3072, True, 2048) == (320, 256, 0)
-    assert plan(6272, 1024) == (128, 128, 0)
+    assert plan(32768, 3200, 3200, R) == (256, 256, 30208)
+    assert plan(32768, 3200, 12800, R) == (256, 256, 30208)
+    # C2 (6272 tokens, hidden 1024): QKV is ONE round of 240 320 x 256 tiles; N = 1024 -> 128 x 128;
+    # fc1 = one round of 320 x 256 tiles over 5120 rows + small tiles instead of two rounds of 256 x 256
+    assert plan(6272, 3072, 1024, Q, 2048) == (320, 256, 0)
+    assert plan(6272, 1024, 1024, R) == (128, 128, 0)
+    assert plan(6272, 4096, 1024, G) == (320, 256, 5120)
+    # C3 (73 896 tokens, hidden 1024): the residual epilogue against K = 1024 goes to the small tile,
+    # against K = 4096 it stays on the large one
+    assert plan(73896, 1024, 1024, R) == (128, 128, 0)
+    assert plan(73896, 1024, 4096, R) == (256, 256, 0)
     # Q | K columns that do not end on a 256-column boundary: the 256 x 128 tile, never cut
-    assert plan(13540, 960, True, 640) == (256, 128, 0)
-    # a QKV projection that is cut (13 540 x 1536: 318 tiles -> 1 round + tail)
-    assert plan(13540, 1536, True, 1024) == (256, 256, 10752)
+    assert plan(13540, 960, 320, Q, 640) == (256, 128, 0)
+    # a QKV projection that is cut (9124 x 2304 at K = 768)
+    assert plan(9124, 2304, 768, Q, 1536) == (256, 256, 7168)
     # a chip with fewer units changes the rounds, hence the plan
-    assert plan(32768, 3200) != B.epd_probe_gemm_plan(32768, 3200, compute_units=208)
-    for bad in [(0, 128), (128, 0), (128, 128, True, 0), (128, 128, True, 256)]:
+    assert plan(32768, 3200, 3200, R) != B.epd_probe_gemm_plan(32768, 3200, 3200, R, compute_units=208)
+    for bad in [(0, 128, 64), (128, 0, 64), (128, 128, 0), (128, 128, 64, 4), (128, 128, 64, -1), (128, 128, 64, Q, 0), (128, 128, 64, Q, 256)]:
         with pytest.raises(B.EpdError):
             B.epd_probe_gemm_plan(*bad, compute_units=256)

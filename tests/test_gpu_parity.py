@@ -175,21 +175,23 @@ def test_bf16_every_gemm_tile_variant(tile):
     parity(cfg, [(1, 20, 30), (1, 2, 2), (1, 26, 22), (1, 8, 8), (1, 4, 16)], gemm_tile=tile)
 
 
-@pytest.mark.parametrize("extra, mlp, qkv_plan, fc1_plan", [
-    ([], 2048, (256, 10752), (320, 10240)),
-    ([(1, 44, 66)], 1280, (320, 13440), (256, 13056)),
+@pytest.mark.parametrize("extra, qkv_plan, fc1_plan", [
+    ([], (256, 7168), (320, 6720)),
+    ([(1, 44, 66), (1, 66, 44)], (320, 8960), (128, 0)),
 ])
-def test_bf16_launches_cut_into_large_tile_body_and_small_tile_tail(extra, mlp, qkv_plan, fc1_plan):
+def test_bf16_launches_cut_into_large_tile_body_and_small_tile_tail(extra, qkv_plan, fc1_plan):
     # token counts at which the launcher cuts the QKV projection (rotary table, V^T column map and
-    # folded-RMSNorm row sums all indexed from the cut) and the first MLP GEMM behind the last full
-    # round of a large tile and finishes the rows with 128 x 128 tiles -- once with a 256 x 256 and
-    # once with a 320 x 256 body each; the plan is read back from the library, not assumed
+    # folded-RMSNorm row sums all indexed from the cut) behind the last full round of a large tile
+    # and finishes the rows with 128 x 128 tiles -- once with a 256 x 256 and once with a 320 x 256
+    # body -- and, in the first case, the first MLP GEMM as well; the plan is read back from the
+    # library, not assumed.  (The residual GEMMs are cut in the full-depth C5 test, the first MLP
+    # GEMM with a 320 x 256 body also in the two-layer C2 test below.)
     from paper_2601_11590_amd import binding as B
-    grids = [(1, 44, 44)] * 5 + [(1, 30, 38), (1, 40, 50), (2, 20, 18)] + extra
-    cfg = small("bf16", num_layers=1, hidden=512, num_heads=8, mlp_dim=mlp, out_dim=256)
+    grids = [(1, 44, 44)] * 4 + [(1, 30, 38), (2, 10, 12)] + extra
+    cfg = small("bf16", num_layers=1, hidden=768, num_heads=12, mlp_dim=3072, out_dim=256)
     T = W.num_tokens(grids)
-    got_qkv = B.epd_probe_gemm_plan(T, 3 * cfg.hidden, True, 2 * cfg.hidden)
-    got_fc1 = B.epd_probe_gemm_plan(T, mlp)
+    got_qkv = B.epd_probe_gemm_plan(T, 3 * cfg.hidden, cfg.hidden, B.EPI_QKV, 2 * cfg.hidden)
+    got_fc1 = B.epd_probe_gemm_plan(T, cfg.mlp_dim, cfg.hidden, B.EPI_GELU)
     log("T=%d: QKV plan %s, fc1 plan %s" % (T, got_qkv, got_fc1))
     assert (got_qkv[0], got_qkv[2]) == qkv_plan and (got_fc1[0], got_fc1[2]) == fc1_plan
     parity(cfg, grids)
