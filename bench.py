@@ -189,7 +189,8 @@ def stored_traffic(name, step):
     return val, "profiles/%s" % os.path.basename(path)
 
 
-def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="item", keep_inputs=False, zero_data=False):
+def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="item", keep_inputs=False, zero_data=False,
+            gemm_tile=-1, attn_rows=0):
     """Times `steps` epd_encode calls of configuration `name`.  Returns a dict of results.
     zero_data: every weight and every input element is zero -- the same kernels and launches on
     operands that toggle no wires, which shows how much of the time on real data is the chip's
@@ -221,6 +222,8 @@ def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="it
             yield lw
 
     enc = B.EpdEncoder(cfg, gw, layer_stream(), max_tokens=T, max_segments=len(cu) - 1, max_items=len(grids))
+    if gemm_tile != -1 or attn_rows != 0:      # tuning experiments: one kernel variant forced for the whole call
+        enc.set_tuning(gemm_tile, attn_rows // 128)
     log("[bench] inputs generated and uploaded in %.1f s; workspace %.2f GB" % (time.perf_counter() - t0, enc.workspace_bytes / 1e9))
     p_dev = B.to_device_patches(patches, cfg.dtype)
     out = torch.empty((Tm, cfg.out_dim), dtype=B.torch_dtype(cfg.dtype), device="cuda:0")
@@ -306,7 +309,7 @@ def measure(name, steps, warmup, in_flight=1, layers_override=None, segments="it
         % (cfg.name, ms_per_step, Tm * steps / dt, tfl, 100 * tfl / PEAK_BF16_TFLOPS, dom, achieved))
     if power.summary():
         log("[bench] board power during the timed steps: mean %.0f W, max %.0f W, limit %.0f W" % (power.summary()["mean_w"], power.summary()["max_w"], power.summary()["cap_w"] or 0))
-    traffic, traffic_src = (None, "depth, segments or data differ from the profiled run") if (layers_override is not None or segments != "item" or in_flight != 1 or zero_data) \
+    traffic, traffic_src = (None, "depth, segments, data or kernel variants differ from the profiled run") if (layers_override is not None or segments != "item" or in_flight != 1 or zero_data or gemm_tile != -1 or attn_rows != 0) \
         else stored_traffic(name, dom)
     res = {
         "name": name, "cfg": cfg, "grids": grids, "cu": cu, "grid": grid, "T": T, "Tm": Tm,
@@ -557,6 +560,11 @@ def main():
     ap.add_argument("--segments", default="item", choices=["item", "frame"],
                     help="attention segments: one per image / clip (default) or one per video frame (windowed attention)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--gemm-tile", type=int, default=-1, choices=[-1, 0, 2, 4, 5],
+                    help="tuning experiment: force one bf16 GEMM tile for every GEMM of the call (0 = 256x256, 2 = 256x128, 4 = 128x128, "
+                         "5 = 320x256; -1 = the library's plan); never the headline")
+    ap.add_argument("--attn-rows", type=int, default=0, choices=[0, 128, 256],
+                    help="tuning experiment: force the attention kernel's query rows per block (0 = the library's choice)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 5 times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--in-flight", type=int, default=1,
@@ -592,10 +600,11 @@ def main():
         log("[bench] copied 5 x 1 GiB (reads 1 GiB and writes 1 GiB per launch)")
         return
 
-    plain = args.layers is None and args.segments == "item" and args.in_flight == 1 and not args.zero_data
+    plain = args.layers is None and args.segments == "item" and args.in_flight == 1 and not args.zero_data and args.gemm_tile == -1 and args.attn_rows == 0
     small = args.config in ("C2", "C3")           # the oracle runs these at full depth in seconds
     head = measure(args.config, args.steps, args.warmup, args.in_flight, args.layers, args.segments,
-                   keep_inputs=small and not args.no_cpu and not args.zero_data, zero_data=args.zero_data)
+                   keep_inputs=small and not args.no_cpu and not args.zero_data, zero_data=args.zero_data,
+                   gemm_tile=args.gemm_tile, attn_rows=args.attn_rows)
     prep, store_res = preprocess_and_store(head, with_store=args.config == "C2" and plain)
     gpu_out = head["out"].float().cpu().numpy()
     stored = stored_rows_parity(args.config, gpu_out) if plain else None
@@ -612,7 +621,7 @@ def main():
         "value": head["value"], "unit": "visual tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": head["workload"], "batches_in_flight": args.in_flight, "patch_tokens": head["T"], "visual_tokens": head["Tm"],
+        "config": {"workload": head["workload"], "batches_in_flight": args.in_flight, "forced_gemm_tile": args.gemm_tile, "forced_attn_rows": args.attn_rows, "patch_tokens": head["T"], "visual_tokens": head["Tm"],
                    "patch_tokens_per_s": head["T"] / (head["ms_per_step"] * 1e-3), "tflops_end_to_end": head["tflops"],
                    "mfma_util_pct_end_to_end": 100 * head["tflops"] / PEAK_BF16_TFLOPS,
                    "attention_flop_share": head["attention_flop_share"]},

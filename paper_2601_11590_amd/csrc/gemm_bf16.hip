@@ -860,7 +860,7 @@ struct TilePlan { int tile, body_rows; double cost; };
 
 static TilePlan plan_tiles(int M, int N, int K, int epi, bool may_split, long cus) {
   TilePlan best = {0, 0, tile_cost(M, N, K, epi, kShape256, cus)};
-  const double keep = 0.97 * best.cost;          // the plain 256 x 256 launch stays unless clearly beaten
+  const double keep = 0.98 * best.cost;          // the plain 256 x 256 launch stays unless clearly beaten
   auto offer = [&](int tile, int body_rows, double cost) {
     if (cost < keep && cost < best.cost) best = {tile, body_rows, cost};
   };
