@@ -456,6 +456,7 @@ def colocation(splits):
     sums = [torch.zeros(65536, dtype=torch.float32, device="cuda:0") for _ in range(2)]
 
     def op_encode(slot, stream, n_cu):
+        encs[slot].set_compute_units(0 if n_cu >= 256 else n_cu)     # the launcher cannot see the stream's mask
         encs[slot].encode(patches, cu, grid, outs[slot])
 
     def op_read(slot, stream, n_cu):

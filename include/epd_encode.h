@@ -276,6 +276,14 @@ epd_status epd_encode_debug_hidden(epd_handle h, void* out_T_by_D_f32, void* str
  * stated tolerances under every setting; they are bit-identical only under the same setting. */
 epd_status epd_encode_set_tuning(epd_handle h, int32_t gemm_tile, int32_t attn_groups);
 
+/* Co-location (section 3.5, "Physical Co-Location and Spatial Multiplexing": stages share one
+ * device): tell the handle that its following epd_encode calls run on a stream that is masked to
+ * `compute_units` compute units (hipExtStreamCreateWithCUMask), so that the GEMM launcher counts
+ * its rounds of tiles for that many units instead of the whole device -- a stream's mask is not
+ * visible to the library.  0 = the whole device (the default).  Changes the launch plans only,
+ * never a result beyond rounding.  EPD_ERR_INVALID_ARG outside 0 .. 4096 or on a NULL handle. */
+epd_status epd_encode_set_compute_units(epd_handle h, int32_t compute_units);
+
 /* Steps of the path, for per-kernel timing. */
 typedef enum {
   EPD_STEP_PLAN = 0, EPD_STEP_PATCH_EMBED = 1, EPD_STEP_NORM = 2, EPD_STEP_QKV = 3,

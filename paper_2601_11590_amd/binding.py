@@ -56,7 +56,7 @@ class epd_encode_cfg(C.Structure):
 
 
 EXPORTS = ["epd_encode_workspace_bytes", "epd_encode_create", "epd_encode", "epd_encode_destroy",
-           "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing", "epd_encode_set_tuning",
+           "epd_encode_last_error", "epd_encode_debug_hidden", "epd_encode_set_timing", "epd_encode_set_tuning", "epd_encode_set_compute_units",
            "epd_encode_get_timing", "epd_preprocess", "epd_encode_cached", "epd_store_create",
            "epd_store_destroy", "epd_store_last_error", "epd_store_hash", "epd_store_hash_noalloc", "epd_store_lookup", "epd_store_insert",
            "epd_store_stats", "epd_probe_stream_read", "epd_probe_mfma_rate", "epd_probe_gemm_plan"]
@@ -102,6 +102,8 @@ def _load() -> C.CDLL:
     lib.epd_encode_debug_hidden.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.epd_encode_set_timing.restype = C.c_int
     lib.epd_encode_set_timing.argtypes = [C.c_void_p, C.c_int32]
+    lib.epd_encode_set_compute_units.restype = C.c_int
+    lib.epd_encode_set_compute_units.argtypes = [C.c_void_p, C.c_int32]
     lib.epd_probe_stream_read.restype = C.c_int
     lib.epd_probe_stream_read.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.epd_probe_mfma_rate.restype = C.c_int
@@ -286,6 +288,12 @@ def epd_encode_set_tuning(handle, gemm_tile: int, attn_groups: int) -> None:
         raise EpdError(st, epd_encode_last_error(handle))
 
 
+def epd_encode_set_compute_units(handle, compute_units: int) -> None:
+    st = lib.epd_encode_set_compute_units(handle, compute_units)
+    if st != EPD_OK:
+        raise EpdError(st, epd_encode_last_error(handle))
+
+
 def epd_probe_stream_read(buf_ptr: int, nbytes: int, out_ptr: int, blocks: int, stream: int) -> None:
     st = lib.epd_probe_stream_read(buf_ptr, nbytes, out_ptr, blocks, stream)
     if st != EPD_OK:
@@ -456,6 +464,9 @@ class EpdEncoder:
 
     def set_tuning(self, gemm_tile: int = -1, attn_groups: int = 0) -> None:
         epd_encode_set_tuning(self.handle, gemm_tile, attn_groups)
+
+    def set_compute_units(self, compute_units: int = 0) -> None:
+        epd_encode_set_compute_units(self.handle, compute_units)
 
     def close(self) -> None:
         if self.handle is not None:

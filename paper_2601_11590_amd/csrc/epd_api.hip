@@ -230,6 +230,7 @@ struct epd_encoder {
   // timing
   // tuning hook (epd_encode_set_tuning): 0 = the library's own choice
   int tile_cfg = 0;      // k > 0: bf16 GEMM tile variant k - 1
+  int compute_units = 0; // > 0: the calls run on a stream masked to this many compute units
   int attn_groups = 0;   // 1 or 2: 128 or 256 query rows per block of the bf16 attention kernel
   int timed_step = -1;
   std::vector<hipEvent_t> ev;     // pairs (start, stop), created lazily
@@ -502,6 +503,7 @@ epd_status epd_encode(epd_handle h, const void* packed_patches, const int32_t* c
     // operands that live in the workspace may be read past their last row (see make_layout)
     g.overread_ok = (g.A != packed_patches && !g.gather) ? 1 : 0;
     g.tile_cfg = h->tile_cfg;
+    g.compute_units = h->compute_units;
     if (bf) launch_gemm_bf16(g, st); else launch_gemm_f32(g, st);
   };
   auto norm = [&](const void* gma, const void* bta, void* dst) {
@@ -783,6 +785,13 @@ epd_status epd_encode_set_tuning(epd_handle h, int32_t gemm_tile, int32_t attn_g
   }
   h->tile_cfg = gemm_tile + 1;
   h->attn_groups = h->cfg.dtype == EPD_BF16 ? attn_groups : 0;
+  return EPD_OK;
+}
+
+epd_status epd_encode_set_compute_units(epd_handle h, int32_t compute_units) {
+  if (!h) { g_create_error = "handle is NULL"; return EPD_ERR_INVALID_ARG; }
+  if (compute_units < 0 || compute_units > 4096) { h->err = fmt("compute_units %d: 0 (the whole device) or 1 .. 4096", compute_units); return EPD_ERR_INVALID_ARG; }
+  h->compute_units = compute_units;
   return EPD_OK;
 }
 

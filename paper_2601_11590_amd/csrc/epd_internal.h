@@ -62,6 +62,7 @@ struct GemmArgs {
   float stats_inv_dim, stats_eps;
   int tile_cfg;         // bf16 path: 0 = automatic choice, k > 0 = tile variant k - 1 (tuning)
   int group_m;          // bf16 path: row tiles per rasterisation group (set by the launcher)
+  int compute_units;    // bf16 path: compute units the launch will run on (a CU-masked stream); 0 = all of the device's
   int name_tag;         // bf16 path, EPI_RESIDUAL: 1 = the second MLP GEMM (a kernel name of its own in
                         //   profiles; the code is the same)
 };

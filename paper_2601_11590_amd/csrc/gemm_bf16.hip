@@ -799,7 +799,7 @@ static void launch_cfg(const GemmArgs& g, hipStream_t s) {
     // XCD streams all of W.  When the whole grid runs in at most two rounds, number the tiles
     // column by column instead, so that an XCD owns a block of columns: W is then fetched
     // once in total and the (smaller) A once per XCD.
-    const long blocks = (long)T::MINBLK * num_cus();
+    const long blocks = (long)T::MINBLK * (g.compute_units > 0 ? g.compute_units : num_cus());
     if ((long)g.N > 2L * g.M && (long)tiles_m * tiles_n <= 2 * blocks) a.group_m = tiles_m;
   }
   a.group_m = std::min(a.group_m, tiles_m);
@@ -883,7 +883,7 @@ static TilePlan plan_tiles(int M, int N, int K, int epi, bool may_split, long cu
 template <int EPI, int OUT, bool GATHER>
 static void launch_epi(const GemmArgs& g, hipStream_t s) {
   int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1;   // tile_cfg: set by the tuning hook of the C ABI, or by a split
-  if (t != 0 && t != 2 && t != 4 && t != 5) t = plan_tiles(g.M, g.N, g.K, g.epilogue, false, num_cus()).tile;
+  if (t != 0 && t != 2 && t != 4 && t != 5) t = plan_tiles(g.M, g.N, g.K, g.epilogue, false, g.compute_units > 0 ? g.compute_units : num_cus()).tile;
   if (EPI == EPI_QKV && (t == 0 || t == 5) && g.qk_cols % 256 != 0) t = 2;
   switch (t) {
     case 0: launch_cfg<T0, EPI, OUT, GATHER>(g, s); break;
@@ -904,7 +904,7 @@ static bool may_split_rows(const GemmArgs& g) {
 }
 
 void plan_gemm_bf16(const GemmArgs& g, int compute_units, int* tile_rows, int* tile_cols, int* body_rows) {
-  const long cus = compute_units > 0 ? compute_units : num_cus();
+  const long cus = compute_units > 0 ? compute_units : (g.compute_units > 0 ? g.compute_units : num_cus());
   int t = g.tile_cfg > 0 ? g.tile_cfg - 1 : -1, body = 0;
   if (t != 0 && t != 2 && t != 4 && t != 5) {
     const TilePlan p = plan_tiles(g.M, g.N, g.K, g.epilogue, may_split_rows(g), cus);
@@ -918,7 +918,7 @@ void plan_gemm_bf16(const GemmArgs& g, int compute_units, int* tile_rows, int* t
 
 void launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;
-  const TilePlan plan = may_split_rows(g) ? plan_tiles(g.M, g.N, g.K, g.epilogue, true, num_cus()) : TilePlan{0, 0, 0.0};
+  const TilePlan plan = may_split_rows(g) ? plan_tiles(g.M, g.N, g.K, g.epilogue, true, g.compute_units > 0 ? g.compute_units : num_cus()) : TilePlan{0, 0, 0.0};
   if (plan.body_rows <= 0) { launch_gemm_bf16_whole(g, s); return; }
   const int mb = plan.body_rows;
   GemmArgs body = g, tail = g;

@@ -164,6 +164,7 @@ def test_create_rejects_bad_pointers_enums_and_workspace():
     assert B.lib.epd_encode_destroy(None) == B.EPD_ERR_INVALID_ARG
     assert B.lib.epd_encode_set_timing(None, 0) == B.EPD_ERR_INVALID_ARG
     assert B.lib.epd_encode_set_tuning(None, -1, 0) == B.EPD_ERR_INVALID_ARG
+    assert B.lib.epd_encode_set_compute_units(None, 224) == B.EPD_ERR_INVALID_ARG
     assert B.epd_encode_workspace_bytes(B.make_cfg(TINY.replace(head_dim=60), 64, 1, 1)) == 0
 
 

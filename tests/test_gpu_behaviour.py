@@ -243,6 +243,30 @@ def test_tuning_hook_rejects_what_has_no_kernel_and_keeps_the_result_within_tole
         enc.close()
 
 
+def test_compute_unit_hint_changes_launch_plans_only():
+    # the hint for CU-masked streams (co-location): other tile plans, the same result within the
+    # tolerances; values outside 0 .. 4096 are refused and change nothing
+    from paper_2601_11590_amd import binding as B
+    cfg = small("bf16", hidden=512, num_heads=8, mlp_dim=1088)
+    enc, gw, layers = make_encoder(cfg, 512)
+    try:
+        patches = W.packed_patches(cfg, GRIDS)
+        cu, grid = W.metadata(GRIDS)
+        ref = O.encode(cfg, gw, layers, patches, cu, grid)
+        whole = run(enc, cfg, patches, cu, grid)
+        for n in (1, 7, 224):
+            enc.set_compute_units(n)
+            check(cfg, run(enc, cfg, patches, cu, grid), ref, "%d compute units" % n)
+        for bad in (-1, 4097):
+            with pytest.raises(B.EpdError) as ei:
+                enc.set_compute_units(bad)
+            assert ei.value.status == B.EPD_ERR_INVALID_ARG
+        enc.set_compute_units(0)
+        assert np.array_equal(whole, run(enc, cfg, patches, cu, grid)), "0 restores the plans for the whole device"
+    finally:
+        enc.close()
+
+
 def test_c3_full_varlen_batch_one_layer():
     # all 32 images, 73 896 tokens (the maximum batch of the benchmark configurations), one layer
     shaped_case(W.C3.replace(num_layers=1), W.grids_for(W.C3), "32 varlen images, 73896 tokens, L=1")
